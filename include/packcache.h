@@ -1,0 +1,190 @@
+/*
+ * packcache.h -- C ABI of the PackCache hot path for AMD MI355X (gfx950).
+ *
+ * PackCache (arXiv 2601.04359) keeps the KV cache of an autoregressive video generator
+ * small: text and conditioning-image keys are always kept ("condition anchoring",
+ * Sec. 3.4), every past frame keeps a token budget that decays with its temporal
+ * distance (Eq. 4-8), the tokens kept inside a frame are the attention-relevant ones,
+ * dropped tokens are physically removed (Fig. 5(b)), and every kept token retains its
+ * original (t, h, w) rotary position (Sec. 3.4, Eq. 9).  The current frame's queries then
+ * attend to the compacted cache (Eq. 2).
+ *
+ * Conventions shared by every call
+ *   - Return value: PC_OK (0) or a negative pc_status.  pc_last_error_detail() gives a
+ *     thread-local message for the last failing call.  Nothing aborts or throws.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
+ *     The caller owns every buffer.  The library allocates no device memory: scratch is
+ *     a caller-provided device workspace whose size the *_workspace_bytes calls return.
+ *   - Device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream).  No call synchronises the stream; host outputs (segment tables,
+ *     counts) never depend on device results.
+ *   - Tensors are row-major with the head dimension D contiguous and rows dense
+ *     (row stride = D elements); the stride between heads is passed in ELEMENTS.
+ *   - dtype: PC_F32 is the correctness tier (D = 64 or 128), PC_BF16 the fast tier
+ *     (D = 128; MFMA kernels, fp32 accumulation and softmax).
+ *   - Query head h reads KV head h / (Hq / Hkv); Hq must be a multiple of Hkv.
+ */
+#ifndef PACKCACHE_H_
+#define PACKCACHE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pc_status {
+  PC_OK = 0,
+  PC_ERR_NULL = -1,        /* a required pointer is NULL */
+  PC_ERR_SHAPE = -2,       /* a size, stride or segment table is inconsistent */
+  PC_ERR_DTYPE = -3,       /* dtype is not PC_F32 / PC_BF16 */
+  PC_ERR_UNSUPPORTED = -4, /* valid request the kernels do not cover (e.g. bf16 with D != 128) */
+  PC_ERR_BUDGET = -5,      /* negative budget, bad decay factor or mode */
+  PC_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than *_workspace_bytes says */
+  PC_ERR_HIP = -7          /* a HIP runtime call or kernel launch failed */
+} pc_status;
+
+enum { PC_F32 = 0, PC_BF16 = 1 };
+
+/* Kinds of cache segment.  TEXT and COND are the anchors, FRAME is a past frame (the
+ * only kind that is pruned), SELF is an always-kept block of current-frame keys. */
+enum { PC_SEG_TEXT = 0, PC_SEG_COND = 1, PC_SEG_FRAME = 2, PC_SEG_SELF = 3 };
+
+/* One contiguous run of cache rows; the table is the same for every head. */
+typedef struct pc_segment {
+  int32_t start; /* first row */
+  int32_t len;   /* number of rows */
+  int32_t kind;  /* PC_SEG_* */
+  int32_t frame; /* frame id (caller's bookkeeping; copied through) */
+} pc_segment;
+
+#define PC_MAX_SEGMENTS 120
+#define PC_MAX_SELECT_LEN 4096 /* longest FRAME segment the register-resident select handles
+                                  in one wave; longer segments take a slower generic path */
+
+const char* pc_strerror(int status);
+const char* pc_last_error_detail(void);
+int pc_version(void);
+
+/* ---------------------------------------------------------------------------------------
+ * pc_budget -- per-frame token budgets from the temporal decay kernel (Sec. 3.4, Eq. 4-8).
+ * Host only, synchronous.  budget_out is a host array [n_past]; entry d-1 belongs to the
+ * frame at temporal distance d (d = 1 is the most recent past frame).
+ *
+ *   PC_BUDGET_POW    b(d) = min(N, max(b_min, floor(N * gamma^d)))   decay kernel g(d) =
+ *                    gamma^d (Eq. 5) on a full frame of N = n_frame_tokens tokens with the
+ *                    minimum quota as a floor.  gamma is the exact value of the double and
+ *                    the product is floored exactly.
+ *   PC_BUDGET_NORM   Eq. 6: share b_d = gamma^d / sum_{j<=W} gamma^j of a fixed budget of
+ *                    N tokens (B_one), W = n_past.
+ *   PC_BUDGET_HALF   Eq. 7: share b_d = 2^-min(d, W-1); gamma is ignored.
+ *   PC_BUDGET_SLIDE  sliding-window baseline (Sec. 3.3): [N, 0, 0, ...].
+ *
+ * NORM and HALF with a minimum quota b_min > 0 (tokens): if W * b_min > N the oldest
+ * frames get 0 until it fits (FIFO truncation, Sec. 3.4); every remaining frame gets
+ * b_min plus its share of what is left.  Flooring leftovers go to d = 1 so that the
+ * budgets add up to N exactly (Eq. 8).
+ * Errors: PC_ERR_NULL, PC_ERR_BUDGET (mode, N < 0, n_past < 0, b_min < 0, gamma outside
+ * (0, 1] for POW/NORM).
+ */
+enum { PC_BUDGET_POW = 0, PC_BUDGET_NORM = 1, PC_BUDGET_HALF = 2, PC_BUDGET_SLIDE = 3 };
+int pc_budget(int mode, int n_frame_tokens, int n_past, double gamma, int b_min,
+              int32_t* budget_out /* host [n_past] */);
+
+/* ---------------------------------------------------------------------------------------
+ * pc_rope3d -- 3D rotary embedding, in place (the operator R of Eq. 2; positions are the
+ * token's own (t, h, w), which compaction never changes: Sec. 3.4, Eq. 9).
+ *   x    dev, [H][n][D] of dtype, head stride stride_h elements; rotated in place.
+ *   pos  dev, int32 [n][3] = (t, h, w) per row, already scaled by the caller.
+ * D is cut into contiguous sections sec_t + sec_h + sec_w = D (all even).  Pair i of a
+ * section of width s is dims (2i, 2i+1) and turns by pos_axis * base^(-2i/s).  Angles are
+ * formed in fp64, the rotation in fp32.  A rebase by (-dt, 0, 0) is the same call with
+ * pos = (-dt, 0, 0): rotations compose.
+ * Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE (sections, D > 256, stride), PC_ERR_HIP.
+ */
+int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride_h,
+              const int32_t* pos, int sec_t, int sec_h, int sec_w, double base, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * pc_score -- importance of every cached key: the softmax probability it receives
+ * (Eq. 2 probabilities, softmax over ALL Nk keys presented), summed over the n_qs scoring
+ * queries and over the query heads of its KV group.  The paper only asks for
+ * "attention-relevant" tokens (Sec. 3.4); this column mass is the reading built here.
+ *   Qs     dev, [Hq][n_qs][D]  scoring queries (already rotated), head stride q_stride_h
+ *   K      dev, [Hkv][Nk][D]   cached keys (already rotated), head stride k_stride_h
+ *   lse    dev or NULL, fp32 [Hq][n_qs]: natural-log sum-exp of each query's scaled logits
+ *          over the same Nk keys.  NULL: computed here (one extra QK^T pass).
+ *   score  dev, fp32 [Hsel][Nk], head stride score_stride_h; Hsel = Hkv, or 1 when
+ *          share_heads != 0 (mass summed over the KV heads as well).
+ * Summation order is fixed (no atomics): results are bit-reproducible.
+ * Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE, PC_ERR_UNSUPPORTED, PC_ERR_WORKSPACE,
+ * PC_ERR_HIP.
+ */
+size_t pc_score_workspace_bytes(int Hq, int Hkv, int n_qs, int Nk, int share_heads);
+int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hkv, int n_qs, int Nk,
+             int D, int64_t q_stride_h, int64_t k_stride_h, float scale, const float* lse,
+             float* score, int64_t score_stride_h, int share_heads, void* ws,
+             size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * pc_compact_plan -- host half of compaction: the segment table and key count after
+ * compaction (anchors and SELF at full length, a FRAME segment at min(len, budget)).
+ * seg_in/budget/seg_out are host arrays [n_seg]; budget entries of non-FRAME segments
+ * are ignored.  Segments must tile [0, Nk_in) in order.
+ * Errors: PC_ERR_NULL, PC_ERR_SHAPE, PC_ERR_BUDGET.
+ */
+int pc_compact_plan(const pc_segment* seg_in, int n_seg, const int32_t* budget,
+                    pc_segment* seg_out, int32_t* Nk_out);
+
+/* ---------------------------------------------------------------------------------------
+ * pc_compact -- per-frame top-k selection and physical compaction (Sec. 3.4, Fig. 5(b)).
+ * For every selection head and every FRAME segment the budget[s] rows with the largest
+ * score are kept (equal scores: lower row index first); all other rows of the segment
+ * are removed.  Kept rows stay in their original order; K, V and pos rows are moved
+ * bit-for-bit, so every token keeps its (t, h, w).
+ *   K, V      dev, [Hkv][cap][D] of dtype, head stride kv_stride_h
+ *   pos       dev, int32 [Hsel][cap][3], head stride pos_stride_h (elements)
+ *   score     dev, fp32 [Hsel][Nk_in], head stride score_stride_h; finite, >= 0
+ *   seg_in    host [n_seg], budget host [n_seg]   (see pc_compact_plan)
+ *   K_out, V_out, pos_out   dev, same layout with strides kv_out_stride_h /
+ *             pos_out_stride_h.  They may be the input buffers themselves (all three or
+ *             none): the compaction is then done in place.  Partial overlap is an error
+ *             the library cannot detect.
+ *   idx_out   dev or NULL, int32 [Hsel][Nk_out], head stride idx_stride_h: source row of
+ *             every packed row (ascending).
+ *   seg_out   host [n_seg] or NULL, Nk_out host or NULL: as from pc_compact_plan.
+ * Hsel = Hkv (every KV head keeps its own rows; counts are equal so tensors stay
+ * rectangular) or 1 when share_heads != 0 (one selection for all heads).
+ * Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE (n_seg > PC_MAX_SEGMENTS, strides,
+ * table), PC_ERR_BUDGET, PC_ERR_WORKSPACE, PC_ERR_HIP.
+ */
+size_t pc_compact_workspace_bytes(int Hkv, int Nk_in, int share_heads);
+int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,
+               int64_t kv_stride_h, int64_t pos_stride_h, const float* score,
+               int64_t score_stride_h, const pc_segment* seg_in, int n_seg,
+               const int32_t* budget, int share_heads, void* K_out, void* V_out,
+               int32_t* pos_out, int64_t kv_out_stride_h, int64_t pos_out_stride_h,
+               int32_t* idx_out, int64_t idx_stride_h, pc_segment* seg_out, int32_t* Nk_out,
+               void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * pc_frame_attn -- attention of one frame's queries over the keys presented (Eq. 2):
+ * O = softmax(Q K^T * scale) V.  K is already rotated; for the current frame's queries
+ * against anchors and earlier frames the causal mask of Eq. 2 hides nothing, so no mask
+ * is applied.  The same call serves the packed and the full ("dense") cache.
+ *   Q  dev [Hq][Nq][D], K, V dev [Hkv][Nk][D], O dev [Hq][Nq][D] (dtype; bf16 is rounded
+ *   to nearest even), lse dev or NULL fp32 [Hq][Nq] = ln sum_j exp(scale * q.k_j).
+ * Nk >= 1, Nq >= 1.  Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE, PC_ERR_UNSUPPORTED,
+ * PC_ERR_WORKSPACE, PC_ERR_HIP.
+ */
+size_t pc_frame_attn_workspace_bytes(int Hq, int Nq, int Nk, int D);
+int pc_frame_attn(const void* Q, const void* K, const void* V, int dtype, int Hq, int Hkv,
+                  int Nq, int Nk, int D, int64_t q_stride_h, int64_t kv_stride_h,
+                  int64_t o_stride_h, float scale, void* O, float* lse, void* ws,
+                  size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PACKCACHE_H_ */

@@ -1,0 +1,186 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+Serves both the HIP path and the CPU oracle and therefore holds none of the method's
+arithmetic: only random draws, the storage rounding of the inputs, segment tables and
+token coordinates.  Shapes follow Sec. 4.1 of the paper (a 48x84 latent token grid per
+frame at 384x672, a few hundred prompt tokens, a conditioning image of one frame) and
+the attention structure follows Sec. 3.2 (anchors attract attention, attention to past
+frames decays with temporal distance).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+SEG_TEXT, SEG_COND, SEG_FRAME, SEG_SELF = 0, 1, 2, 3
+
+
+def to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest bfloat16 (ties to even), kept as float32."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = (u + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)
+    return r.view(np.float32)
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """uint16 bit patterns of float32 values that are exactly representable in bfloat16."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    assert not np.any(u & np.uint32(0xFFFF)), "value is not a bfloat16"
+    return (u >> np.uint32(16)).astype(np.uint16)
+
+
+def bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.asarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def segment_table(n_text: int, n_frame: int, n_past: int) -> list[tuple[int, int, int, int]]:
+    """[text | conditioning image | oldest past frame ... newest past frame]."""
+    segs = [(0, n_text, SEG_TEXT, -1), (n_text, n_frame, SEG_COND, 0)]
+    at = n_text + n_frame
+    for f in range(1, n_past + 1):
+        segs.append((at, n_frame, SEG_FRAME, f))
+        at += n_frame
+    return segs
+
+
+def grid_positions(frame: int, gh: int, gw: int, t0: int) -> np.ndarray:
+    """(t, h, w) of a frame's tokens in raster order, latent coordinates scaled by
+    (4, 8, 8) as in Sec. 3.1."""
+    r, c = np.meshgrid(np.arange(gh), np.arange(gw), indexing="ij")
+    t = np.full(gh * gw, t0 + 4 * frame)
+    return np.stack([t, 8 * r.ravel(), 8 * c.ravel()], axis=1).astype(np.int32)
+
+
+def cache_positions(n_text: int, gh: int, gw: int, n_past: int) -> np.ndarray:
+    """Text token i sits at (i, i, i); visual frames follow, conditioning image = frame 0."""
+    i = np.arange(n_text, dtype=np.int32)
+    rows = [np.stack([i, i, i], axis=1)]
+    for f in range(0, n_past + 1):
+        rows.append(grid_positions(f, gh, gw, n_text))
+    return np.concatenate(rows).astype(np.int32)
+
+
+def low_frequency_dims(sections: tuple[int, int, int], pairs: int = 4) -> np.ndarray:
+    """The last `pairs` rotary pairs of every section: the slowest-turning dims, on which
+    a direction shared by queries and keys survives the rotation."""
+    dims, off = [], 0
+    for s in sections:
+        for i in range(s // 2 - pairs, s // 2):
+            dims += [off + 2 * i, off + 2 * i + 1]
+        off += s
+    return np.asarray(dims)
+
+
+@dataclass
+class Workload:
+    name: str
+    dtype: str                      # "f32" | "bf16"
+    Hq: int
+    Hkv: int
+    D: int
+    n_text: int
+    gh: int
+    gw: int
+    n_past: int
+    gamma: float
+    b_min: int
+    Q: np.ndarray                   # [Hq][Nq][D] float32 (bf16-representable when dtype == bf16)
+    K: np.ndarray                   # [Hkv][Nk][D]
+    V: np.ndarray                   # [Hkv][Nk][D]
+    pos_k: np.ndarray               # [Nk][3] int32
+    pos_q: np.ndarray               # [Nq][3] int32
+    segments: list = field(default_factory=list)
+    sections: tuple | None = None   # rotary split of D over (t, h, w); None: no RoPE
+    base: float = 10000.0
+    score_rows: np.ndarray | None = None   # query rows that score (same for every head)
+
+    @property
+    def n_frame(self) -> int:
+        return self.gh * self.gw
+
+    @property
+    def Nk(self) -> int:
+        return self.K.shape[1]
+
+    @property
+    def Nq(self) -> int:
+        return self.Q.shape[1]
+
+    @property
+    def scale(self) -> float:
+        return float(self.D) ** -0.5
+
+
+def strided_rows(nq: int, n_sample: int) -> np.ndarray:
+    """Scoring subset: n_sample query rows spread evenly over the frame."""
+    n = min(nq, n_sample)
+    return (np.arange(n, dtype=np.int64) * nq) // n
+
+
+def config1(seed: int = 0) -> Workload:
+    """Tiny fp32 case: 2 query heads, 1 KV head, D = 64; 16 text + 8x8 conditioning
+    image + 4 past frames of 8x8; anchor keys pulled toward the query mean."""
+    rng = np.random.default_rng(seed)
+    hq, hkv, d, n_text, gh, gw, n_past = 2, 1, 64, 16, 8, 8, 4
+    n = gh * gw
+    nk = n_text + n * (1 + n_past)
+    Q = rng.standard_normal((hq, n, d)).astype(np.float32)
+    K = rng.standard_normal((hkv, nk, d)).astype(np.float32)
+    V = rng.standard_normal((hkv, nk, d)).astype(np.float32)
+    qmean = Q.reshape(-1, d).mean(axis=0)
+    K[:, : n_text + n, :] += np.float32(0.5) * qmean[None, None, :]
+    return Workload("c1", "f32", hq, hkv, d, n_text, gh, gw, n_past, 0.7, 8, Q, K, V,
+                    cache_positions(n_text, gh, gw, n_past), grid_positions(n_past + 1, gh, gw, n_text),
+                    segment_table(n_text, n, n_past), None, 10000.0, np.arange(n))
+
+
+def frame_layer(name: str, seed: int, hq: int, hkv: int, d: int, n_text: int, gh: int, gw: int,
+                n_past: int, gamma: float, b_min: int, sections: tuple[int, int, int],
+                n_score: int = 512, dtype: str = "bf16") -> Workload:
+    """One attention layer at frame n_past + 1 in the style of the frame-24 / frame-48
+    configurations: V ~ N(0,1); K ~ N(0,1) plus, for the past frame at distance dist,
+    0.3 * 0.9^dist along a unit direction u of its KV group (0.5 for the anchors);
+    Q ~ N(0,1) plus sqrt(D) * u, so that u is the query mean direction and the mean logit
+    of a segment is shifted by exactly its bias magnitude.  u lives on the slowest rotary
+    pairs, so the structure survives 3D RoPE whichever side of it the data is read."""
+    rng = np.random.default_rng(seed)
+    n = gh * gw
+    nk = n_text + n * (1 + n_past)
+    rep = hq // hkv
+    lf = low_frequency_dims(sections)
+    u = np.zeros((hkv, d), np.float32)
+    u[:, lf] = rng.standard_normal((hkv, lf.size)).astype(np.float32)
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    K = rng.standard_normal((hkv, nk, d), dtype=np.float32)
+    V = rng.standard_normal((hkv, nk, d), dtype=np.float32)
+    Q = rng.standard_normal((hq, n, d), dtype=np.float32)
+    K[:, : n_text + n, :] += np.float32(0.5) * u[:, None, :]
+    for f in range(1, n_past + 1):
+        dist = n_past + 1 - f
+        a = n_text + n * f
+        K[:, a:a + n, :] += np.float32(0.3 * 0.9 ** dist) * u[:, None, :]
+    for h in range(hq):
+        Q[h] += np.float32(np.sqrt(d)) * u[h // rep][None, :]
+    if dtype == "bf16":
+        Q, K, V = to_bf16(Q), to_bf16(K), to_bf16(V)
+    return Workload(name, dtype, hq, hkv, d, n_text, gh, gw, n_past, gamma, b_min, Q, K, V,
+                    cache_positions(n_text, gh, gw, n_past), grid_positions(n_past + 1, gh, gw, n_text),
+                    segment_table(n_text, n, n_past), sections, 10000.0, strided_rows(n, n_score))
+
+
+def config2(seed: int = 1000, n_past: int = 23, hq: int = 16, hkv: int = 4) -> Workload:
+    """Single layer at frame 24 (n_past = 23) or frame 48 (n_past = 47): 48x84 tokens per
+    frame, 256 text tokens, D = 128 split 32/48/48, gamma 0.85, minimum quota 512."""
+    return frame_layer(f"frame{n_past + 1}", seed, hq, hkv, 128, 256, 48, 84, n_past, 0.85, 512,
+                       (32, 48, 48))
+
+
+def midsize(seed: int = 7, dtype: str = "bf16", n_past: int = 6, hq: int = 8, hkv: int = 2,
+            gh: int = 12, gw: int = 21, n_text: int = 40, b_min: int = 32,
+            gamma: float = 0.85) -> Workload:
+    """A scaled-down frame layer the oracle finishes in seconds; sizes are deliberately
+    ragged (252 tokens per frame, 40 text tokens) so tiles have tails."""
+    return frame_layer("mid", seed, hq, hkv, 128, n_text, gh, gw, n_past, gamma, b_min, (32, 48, 48),
+                       n_score=100, dtype=dtype)

@@ -1,0 +1,393 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Every check here is independent of the oracle's own formulas: values the paper prints
+(tests/golden/), closed forms, library routines (scipy softmax / logsumexp, complex
+multiplication for 1D RoPE), brute force on tiny inputs, and invariants.
+"""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy.special import logsumexp, softmax
+
+import oracle as orc
+from paper_2601_04359_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _lines(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+
+
+# ----------------------------------------------------------------------------- budgets
+def test_halflife_series_printed_under_eq7():
+    for row in _lines("halflife_series.txt"):
+        w, shares = int(row[0]), [Fraction(s) for s in row[1:]]
+        assert sum(shares) == 1
+        b_one = 4096                                  # divisible by every denominator
+        got = orc.budget_half(b_one, w)
+        assert got == [int(b_one * s) for s in shares]
+        assert sum(got) == b_one                      # Eq. 8
+
+
+def test_halflife_differs_from_eq6_at_half():
+    # Eq. 6 with rho = 1/2 and W = 2 gives (2/3, 1/3), not the (1/2, 1/2) of Eq. 7.
+    assert orc.budget_norm(3000, 2, 0.5) == [2000, 1000]
+    assert orc.budget_half(3000, 2) == [1500, 1500]
+
+
+@pytest.mark.parametrize("rho", [0.5, 0.7, 0.85, 0.95])
+@pytest.mark.parametrize("w", [1, 2, 5, 12, 47])
+def test_norm_allocation_geometric_closed_form(rho, w):
+    b_one = 4084
+    t = orc.budget_norm(b_one, w, rho)
+    assert sum(t) == b_one and len(t) == w           # Eq. 6 / Eq. 8: shares sum to one
+    assert all(t[i] >= t[i + 1] for i in range(w - 1))
+    # geometric series: sum_{j=1..W} rho^j = rho (1 - rho^W) / (1 - rho)
+    for d in range(2, w + 1):
+        share = rho ** d * (1 - rho) / (rho * (1 - rho ** w))
+        assert abs(t[d - 1] - b_one * share) <= 1.0 + 1e-9
+    # flooring leftovers (< W tokens) sit on the most recent frame
+    share1 = rho * (1 - rho) / (rho * (1 - rho ** w))
+    assert 0 <= t[0] - b_one * share1 < w
+
+
+def test_paper_cache_budget_8417():
+    g = {k: int(v) for k, v in _lines("cache_budget_tokens.txt")}
+    for w in (1, 3, 6, 12):
+        for t in (orc.budget_half(g["frame_tokens"], w), orc.budget_norm(g["frame_tokens"], w, 0.5),
+                  orc.budget_slide(g["frame_tokens"], w)):
+            assert g["text_tokens"] + g["frame_tokens"] + sum(t) == g["total_budget"]
+
+
+def test_min_quota_and_fifo_truncation():
+    # W * b_min > B_one: the oldest frames fall out of the window (Sec. 3.4).
+    t = orc.budget_norm(1000, 6, 0.5, q_min=300)
+    assert t[3:] == [0, 0, 0] and sum(t) == 1000 and min(t[:3]) >= 300
+    t = orc.budget_half(1000, 6, q_min=100)
+    assert sum(t) == 1000 and min(t) >= 100
+    assert all(t[i] >= t[i + 1] for i in range(5))
+
+
+def test_pow_budget_values():
+    # 64 * 0.7^d = 44.8, 31.36, 21.952, 15.3664 (hand arithmetic); floor 8 never binds.
+    assert orc.budget_pow(64, 4, 0.7, 8) == [44, 31, 21, 15]
+    # 4032 * 0.85 = 3427.2; 4032 * 0.85^2 = 2913.12; far frames sit on the 512 floor.
+    b = orc.budget_pow(4032, 23, 0.85, 512)
+    assert b[:2] == [3427, 2913] and b[-1] == 512 and sum(b) == 25224
+    assert [sum(orc.budget_pow(4032, 47, g, 512)) for g in (0.7, 0.85, 0.95)] == [29328, 37512, 70326]
+    assert all(b[i] >= b[i + 1] for i in range(len(b) - 1))
+    # degenerate ends: gamma = 1 or a floor above the frame size keep everything
+    assert orc.budget_pow(100, 3, 1.0, 0) == [100, 100, 100]
+    assert orc.budget_pow(100, 3, 0.5, 1000) == [100, 100, 100]
+    assert orc.budget_pow(100, 0, 0.5, 10) == []
+
+
+def test_pow_budget_exact_at_integer_products():
+    # 4096 * 0.5^d is an exact integer: a float pow that lands a hair below would floor wrong.
+    assert orc.budget_pow(4096, 12, 0.5, 0) == [4096 >> d for d in range(1, 13)]
+
+
+def test_heatmap_segment_table_example():
+    bounds = [int(v) for v in _lines("heatmap_segments.txt")[0]]
+    segs = synth.segment_table(bounds[1], bounds[2] - bounds[1], 2)
+    assert [s[0] for s in segs] + [segs[-1][0] + segs[-1][1]] == bounds[:5]
+    # with every budget at full length compaction leaves the table unchanged
+    assert orc.packed_segments(segs, [s[1] for s in segs]) == segs
+
+
+# ----------------------------------------------------------------------------- RoPE
+SEC = (32, 48, 48)
+
+
+def _rand_pos(rng, n):
+    return np.stack([rng.integers(0, 200, n), rng.integers(0, 400, n), rng.integers(0, 700, n)], 1)
+
+
+def test_rope_zero_position_is_identity_and_norms_are_kept():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((3, 10, 128))
+    assert np.array_equal(orc.rope3d(x, np.zeros((10, 3), int), SEC, 1e4), x)
+    y = orc.rope3d(x, _rand_pos(rng, 10), SEC, 1e4)
+    n0 = x[..., 0::2] ** 2 + x[..., 1::2] ** 2
+    n1 = y[..., 0::2] ** 2 + y[..., 1::2] ** 2
+    np.testing.assert_allclose(n1, n0, rtol=1e-12)
+
+
+def test_rope_single_axis_is_textbook_1d_rope_in_complex_form():
+    # Only the t axis moves and the t section spans the whole vector: x_pair * e^{i p theta}
+    rng = np.random.default_rng(1)
+    d, n = 64, 7
+    x = rng.standard_normal((2, n, d))
+    p = rng.integers(0, 500, n)
+    pos = np.stack([p, np.zeros(n, int), np.zeros(n, int)], 1)
+    y = orc.rope3d(x, pos, (d, 0, 0), 1e4)
+    theta = 1e4 ** (-np.arange(0, d, 2) / d)
+    z = (x[..., 0::2] + 1j * x[..., 1::2]) * np.exp(1j * p[None, :, None] * theta[None, None, :])
+    np.testing.assert_allclose(y[..., 0::2], z.real, atol=1e-12)
+    np.testing.assert_allclose(y[..., 1::2], z.imag, atol=1e-12)
+
+
+def test_rope_sections_use_their_own_axis():
+    # moving only h must leave the t and w sections untouched, and vice versa
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((1, 5, 128))
+    for axis, (lo, hi) in enumerate([(0, 32), (32, 80), (80, 128)]):
+        pos = np.zeros((5, 3), int)
+        pos[:, axis] = rng.integers(1, 300, 5)
+        y = orc.rope3d(x, pos, SEC, 1e4)
+        same = np.ones(128, bool)
+        same[lo:hi] = False
+        assert np.array_equal(y[..., same], x[..., same])
+        assert not np.allclose(y[..., lo:hi], x[..., lo:hi])
+        # first pair of a section turns by exactly pos radians (frequency base^0 = 1)
+        c, s = np.cos(pos[:, axis]), np.sin(pos[:, axis])
+        np.testing.assert_allclose(y[0, :, lo], x[0, :, lo] * c - x[0, :, lo + 1] * s, atol=1e-12)
+
+
+def test_rope_logits_depend_on_relative_position_only():
+    # <R_p q, R_p' k> is unchanged when every position moves by the same offset: this
+    # is also why the temporal rebase of Eq. 9 leaves attention unchanged.
+    rng = np.random.default_rng(3)
+    q, k = rng.standard_normal((1, 6, 128)), rng.standard_normal((1, 9, 128))
+    pq, pk = _rand_pos(rng, 6), _rand_pos(rng, 9)
+    s0 = orc.rope3d(q, pq, SEC, 1e4)[0] @ orc.rope3d(k, pk, SEC, 1e4)[0].T
+    for shift in ([-12, 0, 0], [40, -8, 16]):
+        sh = np.asarray(shift)
+        s1 = orc.rope3d(q, pq + sh, SEC, 1e4)[0] @ orc.rope3d(k, pk + sh, SEC, 1e4)[0].T
+        np.testing.assert_allclose(s1, s0, atol=1e-9)
+
+
+def test_rope_composes():
+    rng = np.random.default_rng(4)
+    x = rng.standard_normal((2, 4, 128))
+    a, b = _rand_pos(rng, 4), _rand_pos(rng, 4)
+    np.testing.assert_allclose(orc.rope3d(orc.rope3d(x, a, SEC, 1e4), b, SEC, 1e4),
+                               orc.rope3d(x, a + b, SEC, 1e4), atol=1e-10)
+
+
+def test_rope_is_invariant_to_storage_order():
+    rng = np.random.default_rng(5)
+    x, pos = rng.standard_normal((2, 11, 128)), _rand_pos(rng, 11)
+    perm = rng.permutation(11)
+    assert np.array_equal(orc.rope3d(x[:, perm], pos[perm], SEC, 1e4),
+                          orc.rope3d(x, pos, SEC, 1e4)[:, perm])
+
+
+# ----------------------------------------------------------------------------- attention
+def _tiny(seed=0, hq=2, hkv=1, nq=5, nk=13, d=8):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((hq, nq, d)), rng.standard_normal((hkv, nk, d)),
+            rng.standard_normal((hkv, nk, d)))
+
+
+def test_attention_matches_bruteforce_loops():
+    Q, K, V = _tiny(hq=4, hkv=2)
+    O, _ = orc.frame_attn(Q, K, V, 0.3)
+    np.testing.assert_allclose(O, orc.frame_attn_bruteforce(Q, K, V, 0.3), atol=1e-13)
+
+
+def test_attention_matches_bruteforce_on_config1():
+    w = synth.config1()
+    O, _ = orc.frame_attn(w.Q[:, :6], w.K, w.V, w.scale)
+    np.testing.assert_allclose(O, orc.frame_attn_bruteforce(w.Q[:, :6], w.K, w.V, w.scale), atol=1e-12)
+
+
+def test_attention_against_scipy_softmax_and_logsumexp():
+    Q, K, V = _tiny(seed=3, hq=4, hkv=2, nq=9, nk=31, d=16)
+    O, L = orc.frame_attn(Q, K, V, 0.25)
+    for h in range(4):
+        s = 0.25 * Q[h] @ K[h // 2].T
+        np.testing.assert_allclose(O[h], softmax(s, axis=1) @ V[h // 2], atol=1e-13)
+        np.testing.assert_allclose(L[h], logsumexp(s, axis=1), atol=1e-13)
+
+
+def test_softmax_rows_sum_to_one_and_shift_invariance():
+    rng = np.random.default_rng(6)
+    s = rng.standard_normal((7, 50)) * 5
+    p, lse = orc.softmax_rows(s)
+    np.testing.assert_allclose(p.sum(1), 1.0, atol=1e-14)
+    p2, lse2 = orc.softmax_rows(s + 123.0)
+    np.testing.assert_allclose(p2, p, atol=1e-13)
+    np.testing.assert_allclose(lse2 - 123.0, lse, atol=1e-12)
+
+
+def test_attention_closed_forms():
+    Q, K, V = _tiny(seed=7)
+    # all keys equal: uniform probabilities, output = mean of V
+    Ke = np.repeat(K[:, :1], K.shape[1], axis=1)
+    O, L = orc.frame_attn(Q, Ke, V, 0.5)
+    np.testing.assert_allclose(O, np.broadcast_to(V.mean(1)[0], O.shape), atol=1e-13)
+    np.testing.assert_allclose(L, 0.5 * (Q @ Ke[0, 0]) + np.log(K.shape[1]), atol=1e-12)
+    # a single key: output is that value row
+    O1, _ = orc.frame_attn(Q, K[:, 3:4], V[:, 3:4], 0.5)
+    np.testing.assert_allclose(O1, np.broadcast_to(V[0, 3], O1.shape), atol=1e-14)
+    # one key with an overwhelming logit takes all the mass
+    Kb = K.copy()
+    Kb[0, 5] = 0
+    Qb = np.zeros_like(Q)
+    Kb[0, 5, 0], Qb[..., 0] = 100.0, 100.0
+    Ob, _ = orc.frame_attn(Qb, Kb, V, 1.0)
+    np.testing.assert_allclose(Ob, np.broadcast_to(V[0, 5], Ob.shape), atol=1e-12)
+
+
+def test_gqa_head_mapping():
+    # query head h must read KV head h // (Hq/Hkv): compare with per-head single-KV calls
+    Q, K, V = _tiny(seed=8, hq=6, hkv=3)
+    O, _ = orc.frame_attn(Q, K, V, 0.4)
+    for h in range(6):
+        Oh, _ = orc.frame_attn(Q[h:h + 1], K[h // 2:h // 2 + 1], V[h // 2:h // 2 + 1], 0.4)
+        np.testing.assert_allclose(O[h], Oh[0], atol=1e-14)
+
+
+def test_attention_is_invariant_to_key_order():
+    Q, K, V = _tiny(seed=9, nk=40)
+    perm = np.random.default_rng(1).permutation(40)
+    O0, L0 = orc.frame_attn(Q, K, V, 0.35)
+    O1, L1 = orc.frame_attn(Q, K[:, perm], V[:, perm], 0.35)
+    np.testing.assert_allclose(O1, O0, atol=1e-13)
+    np.testing.assert_allclose(L1, L0, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------- score / select / compact
+def test_score_bruteforce_and_total_mass():
+    Q, K, _ = _tiny(seed=10, hq=4, hkv=2, nq=6, nk=17)
+    s = orc.score(Q, K, 0.3)
+    np.testing.assert_allclose(s, orc.score_bruteforce(Q, K, 0.3), atol=1e-13)
+    assert np.all(s >= 0)
+    # every probability row sums to one: total mass per KV head = queries * heads per group
+    np.testing.assert_allclose(s.sum(1), 6 * 2, atol=1e-12)
+    np.testing.assert_allclose(orc.score(Q, K, 0.3, share_heads=True), s.sum(0, keepdims=True), atol=1e-13)
+
+
+def test_score_config1_total_mass_and_anchor_pull():
+    w = synth.config1()
+    s = orc.score(w.Q, w.K, w.scale)[0]
+    np.testing.assert_allclose(s.sum(), w.Hq * w.Nq, atol=1e-10)
+    # the anchor keys were moved toward the query mean, which can only add mass to them
+    n_anchor = w.n_text + w.n_frame
+    K0 = w.K.copy()
+    K0[:, :n_anchor] -= np.float32(0.5) * w.Q.reshape(-1, w.D).mean(0)[None, None, :]
+    assert s[:n_anchor].sum() > orc.score(w.Q, K0, w.scale)[0][:n_anchor].sum()
+
+
+def test_select_against_full_sort_nesting_and_ties():
+    rng = np.random.default_rng(11)
+    s = rng.random(97)
+    prev = set()
+    for k in range(0, 98):
+        idx = orc.select_topk(s, k)
+        assert len(idx) == k and np.all(np.diff(idx) > 0)
+        ref = sorted(sorted(range(97), key=lambda j: (-s[j], j))[:k])
+        assert list(idx) == ref
+        assert prev <= set(idx)                      # top-k is nested in top-(k+1)
+        prev = set(idx)
+    # ties go to the lower index
+    t = np.array([0.5, 0.2, 0.5, 0.5, 0.9, 0.2, 0.5])
+    assert list(orc.select_topk(t, 3)) == [0, 2, 4]
+    assert list(orc.select_topk(t, 5)) == [0, 2, 3, 4, 6]
+    assert list(orc.select_topk(t, 6)) == [0, 1, 2, 3, 4, 6]
+    assert list(orc.select_topk(np.zeros(5), 2)) == [0, 1]
+
+
+def _compact_c1():
+    w = synth.config1()
+    sc = orc.score(w.Q, w.K, w.scale)
+    b = orc.budget_pow(w.n_frame, w.n_past, w.gamma, w.b_min)
+    budgets = [s[1] if s[2] != orc.SEG_FRAME else b[w.n_past - s[3]] for s in w.segments]
+    pos = w.pos_k[None]
+    return w, sc, budgets, orc.compact(w.K, w.V, pos, sc, w.segments, budgets)
+
+
+def test_compact_rows_are_moved_bit_for_bit_and_anchors_kept():
+    w, sc, budgets, (Kp, Vp, pp, idx, segs) = _compact_c1()
+    assert budgets == [16, 64, 15, 21, 31, 44]       # oldest frame first
+    assert Kp.shape[1] == 191 == segs[-1][0] + segs[-1][1]
+    assert np.array_equal(Kp[0], w.K[0][idx[0]]) and np.array_equal(Vp[0], w.V[0][idx[0]])
+    assert np.array_equal(pp[0], w.pos_k[idx[0]])    # every kept token keeps its (t, h, w)
+    assert np.all(np.diff(idx[0]) > 0)
+    n_anchor = w.n_text + w.n_frame
+    assert np.array_equal(idx[0][:n_anchor], np.arange(n_anchor))
+    for (start, length, kind, _), (ps, pl, _, _), b in zip(w.segments, segs, budgets):
+        got = idx[0][ps:ps + pl]
+        assert np.all((got >= start) & (got < start + length)) and pl == min(length, b)
+        if kind == orc.SEG_FRAME:
+            kept = np.zeros(length, bool)
+            kept[got - start] = True
+            seg = sc[0, start:start + length]
+            assert seg[kept].min() >= seg[~kept].max()    # nothing dropped outranks a kept key
+
+
+def test_full_budget_packed_equals_dense():
+    w = synth.config1()
+    sc = orc.score(w.Q, w.K, w.scale)
+    budgets = [s[1] for s in w.segments]
+    Kp, Vp, pp, idx, segs = orc.compact(w.K, w.V, w.pos_k[None], sc, w.segments, budgets)
+    assert np.array_equal(Kp, w.K) and segs == w.segments
+    O0, _ = orc.frame_attn(w.Q, w.K, w.V, w.scale)
+    O1, _ = orc.frame_attn(w.Q, Kp, Vp, w.scale)
+    assert np.array_equal(O0, O1)
+
+
+def test_packed_equals_dense_with_dropped_keys_masked():
+    w, sc, budgets, (Kp, Vp, pp, idx, segs) = _compact_c1()
+    keep = np.zeros((1, w.Nk), bool)
+    keep[0, idx[0]] = True
+    Op, Lp = orc.frame_attn(w.Q, Kp, Vp, w.scale)
+    Om, Lm = orc.frame_attn(w.Q, w.K, w.V, w.scale, keep=keep)
+    np.testing.assert_allclose(Op, Om, atol=1e-13)
+    np.testing.assert_allclose(Lp, Lm, atol=1e-13)
+    # and dropping keys does change the result (the method is an approximation)
+    Od, _ = orc.frame_attn(w.Q, w.K, w.V, w.scale)
+    assert np.abs(Od - Op).max() > 1e-3
+
+
+def test_packed_attention_with_rope_is_invariant_to_packed_storage_order():
+    w = synth.midsize(n_past=2, hq=2, hkv=1, gh=4, gw=5, n_text=6, b_min=4)
+    Kr = orc.rope3d(w.K, w.pos_k, w.sections, w.base)
+    Qr = orc.rope3d(w.Q, w.pos_q, w.sections, w.base)
+    sc = orc.score(Qr, Kr, w.scale)
+    b = orc.budget_pow(w.n_frame, w.n_past, 0.5, 4)
+    budgets = [s[1] if s[2] != orc.SEG_FRAME else b[w.n_past - s[3]] for s in w.segments]
+    Kp, Vp, pp, idx, _ = orc.compact(w.K, w.V, w.pos_k[None], sc, w.segments, budgets)
+    # rotate after packing using the carried positions, in two different storage orders
+    perm = np.random.default_rng(0).permutation(Kp.shape[1])
+    O0, _ = orc.frame_attn(Qr, orc.rope3d(Kp, pp[0], w.sections, w.base), Vp, w.scale)
+    O1, _ = orc.frame_attn(Qr, orc.rope3d(Kp[:, perm], pp[0][perm], w.sections, w.base), Vp[:, perm], w.scale)
+    np.testing.assert_allclose(O1, O0, atol=1e-12)
+    # and equals rotating before packing: carried positions are the original ones
+    O2, _ = orc.frame_attn(Qr, Kr[:, idx[0]], Vp, w.scale)
+    np.testing.assert_allclose(O2, O0, atol=1e-12)
+
+
+def test_share_heads_selection_is_common_to_all_kv_heads():
+    w = synth.midsize(n_past=3, hq=4, hkv=2, gh=4, gw=5, n_text=6, b_min=4)
+    sc = orc.score(w.Q, w.K, w.scale, share_heads=True)
+    budgets = [s[1] if s[2] != orc.SEG_FRAME else 7 for s in w.segments]
+    Kp, Vp, pp, idx, _ = orc.compact(w.K, w.V, w.pos_k[None], sc, w.segments, budgets, share_heads=True)
+    assert idx.shape[0] == 1
+    for g in range(2):
+        assert np.array_equal(Kp[g], w.K[g][idx[0]]) and np.array_equal(Vp[g], w.V[g][idx[0]])
+
+
+def test_rolling_compaction_is_irreversible_and_well_defined():
+    # Re-packing an already packed cache with smaller budgets only ever removes rows.
+    w, sc, budgets, (Kp, Vp, pp, idx, segs) = _compact_c1()
+    sc2 = orc.score(w.Q, Kp, w.scale)
+    b2 = [s[1] if s[2] != orc.SEG_FRAME else max(8, s[1] // 2) for s in segs]
+    K2, V2, p2, idx2, segs2 = orc.compact(Kp, Vp, pp, sc2, segs, b2)
+    assert set(idx[0][idx2[0]]) <= set(idx[0])
+    assert K2.shape[1] == sum(s[1] for s in segs2)
+
+
+def test_bf16_rounding_helpers():
+    x = np.array([1.0, 1.00390625, 1.005859375, -3.1415926, 1e-3, 65280.0])
+    r = orc.round_to_bf16(x)
+    # 1 + 2^-8 is a tie between 1.0 and 1 + 2^-7: goes to even (1.0)
+    assert r[0] == 1.0 and r[1] == 1.0 and r[2] == 1.0078125
+    assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8)
+    bits = synth.bf16_bits(synth.to_bf16(x.astype(np.float32)))
+    np.testing.assert_array_equal(orc.bf16_bits_to_f64(bits), r)
