@@ -1,0 +1,375 @@
+// pc_compact: per-frame top-k selection and physical compaction (Sec. 3.4, Fig. 5(b)).
+//
+//   select   one wavefront per (selection head, segment).  Scores of a past-frame segment
+//            sit in registers (up to 64 per lane); a bit-by-bit radix select on the
+//            order-preserving integer image of the fp32 score finds the k-th largest value
+//            with wave ballots only (no LDS, no atomics); equal scores are taken lowest
+//            index first; the kept indices come out ascending.
+//   gather   HBM-bound.  A work-group owns 32 consecutive packed rows of one KV head:
+//            it loads its K, V and position rows (16 bytes per lane), then stores them.
+//            In place, a work-group may only store once every work-group whose SOURCE rows
+//            lie in its destination range has finished loading.  Work-groups take their
+//            chunk from an atomic ticket, so a chunk only ever waits on chunks with a lower
+//            ticket, which are already running and whose loads wait on nothing.
+#include <limits.h>
+
+#include <algorithm>
+
+#include "common.h"
+
+namespace pc {
+namespace {
+
+constexpr int kGatherRows = 32;   // packed rows per gather work-group
+constexpr int kGatherThreads = 256;
+constexpr int kMaxItems = 8;      // 16-byte items per thread: rows*chunks_per_row*2/threads
+constexpr int kSpinLimit = 1 << 22;
+
+struct SegTable {
+  int32_t n;
+  int32_t start[PC_MAX_SEGMENTS];  // first source row
+  int32_t len[PC_MAX_SEGMENTS];    // source rows
+  int32_t keep[PC_MAX_SEGMENTS];   // rows kept
+  int32_t dst[PC_MAX_SEGMENTS];    // first packed row
+  uint8_t prune[PC_MAX_SEGMENTS];  // 1: past frame with keep < len (needs the select)
+};
+
+// fp32 -> uint32 such that integer order = float order; -0 is folded onto +0 first.
+__device__ __forceinline__ uint32_t order_key(float f) {
+  const uint32_t u = __float_as_uint(f + 0.0f);
+  return u ^ (static_cast<uint32_t>(static_cast<int32_t>(u) >> 31) | 0x80000000u);
+}
+
+__device__ __forceinline__ int popc64(uint64_t v) { return __popcll(v); }
+
+// One wave selects the top `k` of `len` scores.  Keys are register resident when
+// kItems > 0 (len <= 64 * kItems); kItems == 0 re-reads the scores on every pass.
+template <int kItems>
+__device__ void select_wave(const float* __restrict__ sc, int len, int k, int32_t* __restrict__ out,
+                            int start) {
+  const int lane = threadIdx.x;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  constexpr int kRegs = kItems > 0 ? kItems : 1;
+  uint32_t key[kRegs];
+  const int n_iter = kItems > 0 ? kItems : (len + 63) / 64;
+  if constexpr (kItems > 0) {
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+      const int e = i * 64 + lane;
+      key[i] = e < len ? order_key(sc[e]) : 0u;  // 0 is below every real key
+    }
+  }
+  auto key_at = [&](int i) -> uint32_t {
+    if constexpr (kItems > 0) {
+      return key[i];
+    } else {
+      const int e = i * 64 + lane;
+      return e < len ? order_key(sc[e]) : 0u;
+    }
+  };
+  // k-th largest key, most significant bit first
+  uint32_t prefix = 0;
+  int remaining = k;
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t cand = prefix | (1u << bit);
+    int cnt = 0;
+    if constexpr (kItems > 0) {
+#pragma unroll
+      for (int i = 0; i < kItems; ++i) cnt += popc64(__ballot(((key[i] ^ cand) >> bit) == 0u));
+    } else {
+      for (int i = 0; i < n_iter; ++i) cnt += popc64(__ballot(((key_at(i) ^ cand) >> bit) == 0u));
+    }
+    if (cnt >= remaining)
+      prefix = cand;
+    else
+      remaining -= cnt;
+  }
+  // everything above the threshold, then the first `remaining` keys equal to it
+  int out_run = 0, eq_run = 0;
+  auto emit = [&](int i, uint32_t kv) {
+    const int e = i * 64 + lane;
+    const bool valid = e < len;
+    const bool eq = valid && kv == prefix;
+    const uint64_t beq = __ballot(eq);
+    const bool keep = valid && (kv > prefix || (eq && eq_run + popc64(beq & lt_mask) < remaining));
+    const uint64_t bk = __ballot(keep);
+    const int at = out_run + popc64(bk & lt_mask);
+    if (keep && at < k) out[at] = start + e;
+    out_run += popc64(bk);
+    eq_run += popc64(beq);
+  };
+  if constexpr (kItems > 0) {
+#pragma unroll
+    for (int i = 0; i < kItems; ++i)
+      if (i * 64 < len) emit(i, key[i]);
+  } else {
+    for (int i = 0; i < n_iter; ++i) emit(i, key_at(i));
+  }
+}
+
+template <int kItems>
+__global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ score,
+                                                    int64_t score_stride_h, int32_t* __restrict__ idx,
+                                                    int64_t idx_stride_h, SegTable tab) {
+  const int s = blockIdx.x, h = blockIdx.y;
+  const int start = tab.start[s], len = tab.len[s], keep = tab.keep[s];
+  int32_t* out = idx + h * idx_stride_h + tab.dst[s];
+  if (keep <= 0) return;
+  if (!tab.prune[s]) {  // anchors, current frame, or a frame within budget: keep every row
+    for (int e = threadIdx.x; e < len; e += 64) out[e] = start + e;
+    return;
+  }
+  select_wave<kItems>(score + h * score_stride_h + start, len, keep, out, start);
+}
+
+// ---- gather ----------------------------------------------------------------------------------
+struct GatherSync {
+  int32_t ticket;
+  int32_t abort;
+  int32_t pad[62];
+};
+
+__global__ void gather_init(GatherSync* sync, int32_t* flags, int n_flags) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i == 0) {
+    sync->ticket = 0;
+    sync->abort = 0;
+  }
+  if (i < n_flags) flags[i] = 0;
+}
+
+template <bool kInPlace>
+__global__ __launch_bounds__(kGatherThreads) void gather_kernel(
+    const u32x4* __restrict__ K, const u32x4* __restrict__ V, const int32_t* __restrict__ pos,
+    u32x4* __restrict__ Ko, u32x4* __restrict__ Vo, int32_t* __restrict__ pos_o,
+    const int32_t* __restrict__ idx, int64_t idx_stride_h, int share_heads, int Hkv, int Nk_in, int Nk_out,
+    int cpr /* 16-byte chunks per row */, int64_t in_stride_c, int64_t out_stride_c,
+    int64_t pos_stride_h, int64_t pos_out_stride_h, GatherSync* sync, int32_t* flags,
+    int chunks_per_head, SegTable tab) {
+  __shared__ int s_ticket;
+  int work = blockIdx.x;
+  if constexpr (kInPlace) {
+    if (threadIdx.x == 0) s_ticket = atomicAdd(&sync->ticket, 1);
+    __syncthreads();
+    work = s_ticket;
+  }
+  const int h = work % Hkv, cc = work / Hkv;
+  const int hs = share_heads ? 0 : h;
+  const int r0 = cc * kGatherRows;
+  const int r1 = min(r0 + kGatherRows, Nk_out);
+  const int n_items = (r1 - r0) * cpr * 2;
+  const int32_t* idx_h = idx + hs * idx_stride_h;
+
+  // ---- load ----
+  u32x4 val[kMaxItems];
+  int64_t dst_off[kMaxItems];
+#pragma unroll
+  for (int it = 0; it < kMaxItems; ++it) {
+    const int item = it * kGatherThreads + threadIdx.x;
+    dst_off[it] = -1;
+    if (item < n_items) {
+      const int which = item >= (r1 - r0) * cpr;  // 0: K, 1: V
+      const int e = which ? item - (r1 - r0) * cpr : item;
+      const int row = r0 + e / cpr, ch = e % cpr;
+      const int src = min(max(idx_h[row], 0), Nk_in - 1);  // a valid table never needs the clamp
+      if (!kInPlace || src != row) {
+        const u32x4* base = which ? V : K;
+        val[it] = base[h * in_stride_c + static_cast<int64_t>(src) * cpr + ch];
+        dst_off[it] = (static_cast<int64_t>(which) << 62) | (h * out_stride_c + static_cast<int64_t>(row) * cpr + ch);
+      }
+    }
+  }
+  int32_t pval = 0;
+  int64_t pdst = -1;
+  if ((share_heads ? h == 0 : true) && threadIdx.x < (r1 - r0) * 3) {
+    const int row = r0 + threadIdx.x / 3, comp = threadIdx.x % 3;
+    const int src = min(max(idx_h[row], 0), Nk_in - 1);
+    if (!kInPlace || src != row) {
+      pval = pos[hs * pos_stride_h + static_cast<int64_t>(src) * 3 + comp];
+      pdst = hs * pos_out_stride_h + static_cast<int64_t>(row) * 3 + comp;
+    }
+  }
+
+  if constexpr (kInPlace) {
+    // publish "my sources are in registers", then wait for every lower chunk of this head
+    // whose sources may lie in [r0, r1).  Source row of the i-th kept row of a segment is
+    // bounded by start + i <= src <= start + (len - keep) + i.
+    __threadfence();
+    __syncthreads();
+    int32_t* flags_h = flags + h * chunks_per_head;
+    if (threadIdx.x == 0)
+      __hip_atomic_store(&flags_h[cc], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    int row_lo = INT_MAX, row_hi = -1;
+    for (int s = 0; s < tab.n; ++s) {
+      const int a = tab.start[s], b = a + tab.len[s];
+      if (b <= r0 || a >= r1 || tab.keep[s] <= 0) continue;
+      const int slack = tab.len[s] - tab.keep[s];
+      const int i_lo = max(0, r0 - a - slack), i_hi = min(tab.keep[s] - 1, r1 - 1 - a);
+      if (i_lo <= i_hi) {
+        row_lo = min(row_lo, tab.dst[s] + i_lo);
+        row_hi = max(row_hi, tab.dst[s] + i_hi);
+      }
+    }
+    if (row_hi >= 0) {
+      const int c_lo = row_lo / kGatherRows, c_hi = min(row_hi / kGatherRows, cc - 1);
+      for (int c = c_lo + threadIdx.x; c <= c_hi; c += kGatherThreads) {
+        int spins = 0;
+        while (__hip_atomic_load(&flags_h[c], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+          if (__hip_atomic_load(&sync->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+          if (++spins > kSpinLimit) {  // cannot happen (lower tickets never wait to load); never hang
+            __hip_atomic_store(&sync->abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+          }
+          __builtin_amdgcn_s_sleep(2);
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- store ----
+#pragma unroll
+  for (int it = 0; it < kMaxItems; ++it) {
+    if (dst_off[it] >= 0) {
+      u32x4* base = (dst_off[it] >> 62) ? Vo : Ko;
+      base[dst_off[it] & ((1ll << 62) - 1)] = val[it];
+    }
+  }
+  if (pdst >= 0) pos_o[pdst] = pval;
+}
+
+struct WsLayout {
+  size_t idx_off, sync_off, flags_off, total;
+  int chunks_per_head;
+};
+
+WsLayout ws_layout(int Hkv, int Nk_in, int share_heads) {
+  WsLayout w;
+  const int hsel = share_heads ? 1 : Hkv;
+  size_t at = 0;
+  w.idx_off = at;
+  at += align_up(sizeof(int32_t) * static_cast<size_t>(hsel) * Nk_in, 256);
+  w.sync_off = at;
+  at += sizeof(GatherSync);
+  w.flags_off = at;
+  w.chunks_per_head = ceil_div(Nk_in, kGatherRows);
+  at += align_up(sizeof(int32_t) * static_cast<size_t>(Hkv) * w.chunks_per_head, 256);
+  w.total = at;
+  return w;
+}
+
+}  // namespace
+}  // namespace pc
+
+using namespace pc;
+
+extern "C" size_t pc_compact_workspace_bytes(int Hkv, int Nk_in, int share_heads) {
+  if (Hkv <= 0 || Nk_in <= 0) return 0;
+  return ws_layout(Hkv, Nk_in, share_heads).total;
+}
+
+extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,
+                          int64_t kv_stride_h, int64_t pos_stride_h, const float* score,
+                          int64_t score_stride_h, const pc_segment* seg_in, int n_seg,
+                          const int32_t* budget, int share_heads, void* K_out, void* V_out,
+                          int32_t* pos_out, int64_t kv_out_stride_h, int64_t pos_out_stride_h,
+                          int32_t* idx_out, int64_t idx_stride_h, pc_segment* seg_out,
+                          int32_t* Nk_out, void* ws, size_t ws_bytes, void* stream) {
+  PC_REQUIRE(dtype == PC_F32 || dtype == PC_BF16, PC_ERR_DTYPE, "pc_compact: dtype %d", dtype);
+  PC_REQUIRE(Hkv > 0 && D > 0, PC_ERR_SHAPE, "pc_compact: Hkv=%d D=%d", Hkv, D);
+  PC_REQUIRE(n_seg >= 0 && n_seg <= PC_MAX_SEGMENTS, PC_ERR_SHAPE,
+             "pc_compact: n_seg=%d outside [0, %d]", n_seg, PC_MAX_SEGMENTS);
+  pc_segment plan[PC_MAX_SEGMENTS];
+  int32_t nk_out = 0;
+  const int rc = pc_compact_plan(seg_in, n_seg, budget, plan, &nk_out);
+  if (rc != PC_OK) return rc;
+  if (seg_out)
+    for (int s = 0; s < n_seg; ++s) seg_out[s] = plan[s];
+  if (Nk_out) *Nk_out = nk_out;
+  const int nk_in = n_seg ? seg_in[n_seg - 1].start + seg_in[n_seg - 1].len : 0;
+  if (nk_in == 0 || nk_out == 0) return PC_OK;
+
+  const int elt = dtype == PC_BF16 ? 2 : 4;
+  const int row_bytes = D * elt;
+  PC_REQUIRE(row_bytes % 16 == 0 && row_bytes / 16 <= 4 * kMaxItems, PC_ERR_UNSUPPORTED,
+             "pc_compact: row of %d bytes (must be a multiple of 16, at most %d)", row_bytes,
+             64 * kMaxItems);
+  PC_REQUIRE(K && V && pos && score && K_out && V_out && pos_out, PC_ERR_NULL,
+             "pc_compact: K, V, pos, score or an output is NULL");
+  const bool in_place = K_out == K;
+  PC_REQUIRE((V_out == V) == in_place && (pos_out == pos) == in_place, PC_ERR_SHAPE,
+             "pc_compact: outputs must alias the inputs all together or not at all");
+  PC_REQUIRE(!in_place || (kv_out_stride_h == kv_stride_h && pos_out_stride_h == pos_stride_h),
+             PC_ERR_SHAPE, "pc_compact: in-place compaction needs equal input and output strides");
+  const int hsel = share_heads ? 1 : Hkv;
+  PC_REQUIRE(kv_stride_h >= static_cast<int64_t>(nk_in) * D && kv_out_stride_h >= static_cast<int64_t>(nk_out) * D,
+             PC_ERR_SHAPE, "pc_compact: a K/V head stride is smaller than rows*D");
+  PC_REQUIRE(hsel == 1 || (pos_stride_h >= static_cast<int64_t>(nk_in) * 3 &&
+                           pos_out_stride_h >= static_cast<int64_t>(nk_out) * 3 && score_stride_h >= nk_in),
+             PC_ERR_SHAPE, "pc_compact: a pos/score head stride is too small");
+  PC_REQUIRE(idx_out == nullptr || hsel == 1 || idx_stride_h >= nk_out, PC_ERR_SHAPE,
+             "pc_compact: idx head stride %lld < Nk_out", static_cast<long long>(idx_stride_h));
+  const uintptr_t al = reinterpret_cast<uintptr_t>(K) | reinterpret_cast<uintptr_t>(V) |
+                       reinterpret_cast<uintptr_t>(K_out) | reinterpret_cast<uintptr_t>(V_out);
+  PC_REQUIRE(al % 16 == 0 && (kv_stride_h * elt) % 16 == 0 && (kv_out_stride_h * elt) % 16 == 0,
+             PC_ERR_SHAPE, "pc_compact: K/V buffers and head strides must be 16-byte aligned");
+  const WsLayout lay = ws_layout(Hkv, nk_in, share_heads);
+  PC_REQUIRE(ws != nullptr && ws_bytes >= lay.total, PC_ERR_WORKSPACE,
+             "pc_compact: workspace %zu bytes, need %zu", ws_bytes, lay.total);
+  PC_REQUIRE(reinterpret_cast<uintptr_t>(ws) % 16 == 0, PC_ERR_WORKSPACE, "pc_compact: workspace not 16-byte aligned");
+
+  SegTable tab;
+  tab.n = n_seg;
+  int max_prune_len = 0;
+  for (int s = 0; s < n_seg; ++s) {
+    tab.start[s] = seg_in[s].start;
+    tab.len[s] = seg_in[s].len;
+    tab.keep[s] = plan[s].len;
+    tab.dst[s] = plan[s].start;
+    tab.prune[s] = seg_in[s].kind == PC_SEG_FRAME && plan[s].len < seg_in[s].len;
+    if (tab.prune[s]) max_prune_len = std::max(max_prune_len, seg_in[s].len);
+  }
+  for (int s = n_seg; s < PC_MAX_SEGMENTS; ++s) {
+    tab.start[s] = tab.len[s] = tab.keep[s] = tab.dst[s] = 0;
+    tab.prune[s] = 0;
+  }
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  uint8_t* wsb = static_cast<uint8_t*>(ws);
+  int32_t* idx = idx_out ? idx_out : reinterpret_cast<int32_t*>(wsb + lay.idx_off);
+  const int64_t idx_stride = idx_out ? idx_stride_h : nk_in;
+  GatherSync* sync = reinterpret_cast<GatherSync*>(wsb + lay.sync_off);
+  int32_t* flags = reinterpret_cast<int32_t*>(wsb + lay.flags_off);
+
+  const dim3 sgrid(n_seg, hsel);
+  if (max_prune_len <= 256)
+    select_kernel<4><<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab);
+  else if (max_prune_len <= 1024)
+    select_kernel<16><<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab);
+  else if (max_prune_len <= PC_MAX_SELECT_LEN)
+    select_kernel<64><<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab);
+  else
+    select_kernel<0><<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab);
+  PC_CHECK_LAUNCH("pc_compact select");
+
+  const int cpr = row_bytes / 16;
+  const int chunks_per_head = ceil_div(nk_out, kGatherRows);
+  const int64_t in_stride_c = kv_stride_h * elt / 16, out_stride_c = kv_out_stride_h * elt / 16;
+  const dim3 ggrid(chunks_per_head * Hkv);
+  if (in_place) {
+    const int n_flags = Hkv * lay.chunks_per_head;
+    gather_init<<<ceil_div(n_flags, 256), 256, 0, st>>>(sync, flags, n_flags);
+    PC_CHECK_LAUNCH("pc_compact init");
+    gather_kernel<true><<<ggrid, kGatherThreads, 0, st>>>(
+        static_cast<const u32x4*>(K), static_cast<const u32x4*>(V), pos, static_cast<u32x4*>(K_out),
+        static_cast<u32x4*>(V_out), pos_out, idx, idx_stride, share_heads, Hkv, nk_in, nk_out, cpr, in_stride_c,
+        out_stride_c, pos_stride_h, pos_out_stride_h, sync, flags, lay.chunks_per_head, tab);
+  } else {
+    gather_kernel<false><<<ggrid, kGatherThreads, 0, st>>>(
+        static_cast<const u32x4*>(K), static_cast<const u32x4*>(V), pos, static_cast<u32x4*>(K_out),
+        static_cast<u32x4*>(V_out), pos_out, idx, idx_stride, share_heads, Hkv, nk_in, nk_out, cpr, in_stride_c,
+        out_stride_c, pos_stride_h, pos_out_stride_h, sync, flags, lay.chunks_per_head, tab);
+  }
+  PC_CHECK_LAUNCH("pc_compact gather");
+  return PC_OK;
+}

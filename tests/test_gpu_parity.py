@@ -1,0 +1,388 @@
+"""GPU parity: every C-ABI call against the fp64 oracle on the same seeded inputs.
+
+Tolerances
+  * indices, moved rows, positions, segment tables: bit-exact; selected sets may differ
+    from the oracle's only on keys whose oracle score is within 1e-6 of the k-th score;
+  * bf16 attention (bf16 inputs, fp32 accumulation): max |err| <= 2e-2, mean |err| <= 2e-3;
+  * fp32 tier: max |err| <= 1e-5 on outputs of O(1);
+  * bf16 RoPE: one bf16 rounding of the fp32 rotation, |err| <= 2^-8 |x| + 1e-6.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_2601_04359_amd as pk
+from paper_2601_04359_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+BAND = 1e-6
+
+
+def dev(x, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(x))
+    if dtype == "bf16":
+        return t.to(torch.bfloat16).to(DEV)
+    return t.to(DEV)
+
+
+def host(t):
+    return t.detach().to(torch.float32).cpu().numpy() if t.is_floating_point() else t.detach().cpu().numpy()
+
+
+def budgets_for(w, gamma=None, b_min=None):
+    b = pk.pc_budget(pk.PC_BUDGET_POW, w.n_frame, w.n_past, w.gamma if gamma is None else gamma,
+                     w.b_min if b_min is None else b_min)
+    assert b == orc.budget_pow(w.n_frame, w.n_past, w.gamma if gamma is None else gamma,
+                               w.b_min if b_min is None else b_min)
+    return pk.segment_budgets(w.segments, b)
+
+
+def check_selection(idx_gpu, sc_oracle, segments, budgets, band=BAND, other_input=None):
+    """idx_gpu [Hsel][Nk_out] int; sc_oracle [Hsel][Nk] fp64.  Returns #exempted keys.
+    other_input [Hsel][Nk] bool marks keys whose device input bits differ from the oracle's
+    (a rotation that rounded the other way): their scores are not comparable."""
+    exempted = 0
+    plan = orc.packed_segments(segments, budgets)
+    for h in range(sc_oracle.shape[0]):
+        for (start, length, kind, _), (ps, pl, _, _) in zip(segments, plan):
+            got = idx_gpu[h, ps:ps + pl].astype(np.int64)
+            assert np.all(np.diff(got) > 0), "indices must be strictly ascending"
+            assert got.size == 0 or (got[0] >= start and got[-1] < start + length)
+            if kind != orc.SEG_FRAME or pl == length:
+                assert np.array_equal(got, np.arange(start, start + length))
+                continue
+            if pl == 0:
+                continue
+            seg = sc_oracle[h, start:start + length]
+            want = start + orc.select_topk(seg, pl)
+            if np.array_equal(got, want):
+                continue
+            thr = np.sort(seg)[::-1][pl - 1]
+            diff = np.setxor1d(got, want)
+            ok = np.abs(seg[diff - start] - thr) <= band
+            if other_input is not None:
+                ok |= other_input[h, diff]
+            assert np.all(ok), f"head {h} segment at {start}: selection differs outside the {band} band"
+            exempted += diff.size
+    return exempted
+
+
+# ------------------------------------------------------------------------------- RoPE
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("n,H", [(1, 1), (37, 3), (252, 8), (1000, 2)])
+def test_rope3d_parity(dtype, n, H):
+    rng = np.random.default_rng(n * 31 + H)
+    x = rng.standard_normal((H, n, 128)).astype(np.float32)
+    if dtype == "bf16":
+        x = synth.to_bf16(x)
+    pos = np.stack([rng.integers(0, 450, n), rng.integers(0, 380, n), rng.integers(0, 670, n)], 1).astype(np.int32)
+    want = orc.rope3d(x, pos, (32, 48, 48), 1e4)
+    xd = dev(x, dtype)
+    pk.pc_rope3d(xd, dev(pos, None), (32, 48, 48), 1e4)
+    got = host(xd).astype(np.float64)
+    err = np.abs(got - want)
+    if dtype == "bf16":
+        assert np.all(err <= 2.0 ** -8 * np.abs(want) + 1e-6)
+        # the result is the correctly rounded bf16 of the exact rotation almost everywhere
+        assert np.mean(got == orc.round_to_bf16(want)) > 0.999
+    else:
+        assert err.max() <= 2e-6
+
+
+def test_rope3d_negative_shift_undoes_rotation_and_head_stride():
+    # a rebase by (-dt, 0, 0) (Eq. 9) is a rotation with negative position; also exercises
+    # a head stride larger than n*D (capacity > rows)
+    rng = np.random.default_rng(5)
+    cap, n = 64, 50
+    buf = torch.zeros((2, cap, 128), dtype=torch.float32, device=DEV)
+    x = rng.standard_normal((2, n, 128)).astype(np.float32)
+    buf[:, :n] = dev(x, "f32")
+    pos = np.stack([rng.integers(0, 100, n), rng.integers(0, 100, n), rng.integers(0, 100, n)], 1).astype(np.int32)
+    view = buf[:, :n]
+    pk.pc_rope3d(view, dev(pos, None), (32, 48, 48), 1e4)
+    np.testing.assert_allclose(host(view), orc.rope3d(x, pos, (32, 48, 48), 1e4), atol=2e-6)
+    pk.pc_rope3d(view, dev(-pos, None), (32, 48, 48), 1e4)
+    np.testing.assert_allclose(host(view), x, atol=4e-6)
+    assert torch.all(buf[:, n:] == 0)
+
+
+# ------------------------------------------------------------------------------- attention
+def _attn_case(dtype, hq, hkv, nq, nk, d, seed):
+    rng = np.random.default_rng(seed)
+    Q = rng.standard_normal((hq, nq, d)).astype(np.float32)
+    K = rng.standard_normal((hkv, nk, d)).astype(np.float32)
+    V = rng.standard_normal((hkv, nk, d)).astype(np.float32)
+    if dtype == "bf16":
+        Q, K, V = synth.to_bf16(Q), synth.to_bf16(K), synth.to_bf16(V)
+    return Q, K, V
+
+
+def _attn_check(dtype, Q, K, V, scale):
+    hq, nq, d = Q.shape
+    nk = K.shape[1]
+    lse = torch.empty((hq, nq), dtype=torch.float32, device=DEV)
+    O = pk.pc_frame_attn(dev(Q, dtype), dev(K, dtype), dev(V, dtype), nk, scale, lse=lse)
+    Ow, Lw = orc.frame_attn(Q, K, V, scale)
+    err = np.abs(host(O).astype(np.float64) - Ow)
+    lerr = np.abs(host(lse).astype(np.float64) - Lw)
+    if dtype == "bf16":
+        assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
+        assert lerr.max() <= 1e-3
+    else:
+        assert err.max() <= 1e-5, err.max()
+        assert lerr.max() <= 1e-5
+    return err
+
+
+@pytest.mark.parametrize("nq,nk", [(1, 1), (5, 63), (64, 64), (65, 65), (256, 128), (300, 777), (513, 1000)])
+def test_frame_attn_bf16_shapes(nq, nk):
+    Q, K, V = _attn_case("bf16", 4, 2, nq, nk, 128, nq * 1000 + nk)
+    _attn_check("bf16", Q, K, V, 128 ** -0.5)
+
+
+def test_frame_attn_bf16_gqa_groups_and_large_logits():
+    # 3 query heads per KV head; a strong shared direction makes logits reach ~ +-40
+    Q, K, V = _attn_case("bf16", 6, 2, 130, 500, 128, 77)
+    Q[..., :8] += 4.0
+    K[:, ::7, :8] += 4.0
+    Q, K = synth.to_bf16(Q), synth.to_bf16(K)
+    _attn_check("bf16", Q, K, V, 128 ** -0.5)
+
+
+def test_frame_attn_bf16_closed_forms():
+    Q, K, V = _attn_case("bf16", 2, 1, 70, 200, 128, 3)
+    Ke = np.repeat(K[:, :1], 200, axis=1)                     # all keys equal -> mean of V
+    O = host(pk.pc_frame_attn(dev(Q, "bf16"), dev(Ke, "bf16"), dev(V, "bf16"), 200, 0.1))
+    np.testing.assert_allclose(O, np.broadcast_to(V.mean(1)[0], O.shape), atol=4e-3)
+    O1 = host(pk.pc_frame_attn(dev(Q, "bf16"), dev(K[:, 5:6], "bf16"), dev(V[:, 5:6], "bf16"), 1, 0.1))
+    assert np.array_equal(O1, np.broadcast_to(V[0, 5], O1.shape))   # one key -> that value row
+
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("nq,nk", [(1, 1), (64, 336), (70, 33), (130, 191)])
+def test_frame_attn_f32_shapes(d, nq, nk):
+    Q, K, V = _attn_case("f32", 4, 2, nq, nk, d, d + nq + nk)
+    _attn_check("f32", Q, K, V, d ** -0.5)
+
+
+def test_frame_attn_capacity_larger_than_rows():
+    # K/V live in buffers with spare capacity (head stride > Nk*D), as a cache does
+    Q, K, V = _attn_case("bf16", 4, 2, 100, 300, 128, 11)
+    Kb = torch.zeros((2, 512, 128), dtype=torch.bfloat16, device=DEV)
+    Vb = torch.full((2, 512, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    Kb[:, :300], Vb[:, :300] = dev(K, "bf16"), dev(V, "bf16")
+    O = pk.pc_frame_attn(dev(Q, "bf16"), Kb, Vb, 300, 128 ** -0.5)
+    Ow, _ = orc.frame_attn(Q, K, V, 128 ** -0.5)
+    err = np.abs(host(O) - Ow)
+    assert err.max() <= 2e-2 and err.mean() <= 2e-3
+
+
+# ------------------------------------------------------------------------------- score
+def _score_check(w, Qs, K, share=False, lse=None):
+    dt = w.dtype
+    got = host(pk.pc_score(dev(Qs, dt), dev(K, dt), K.shape[1], w.scale, lse=lse, share_heads=share)).astype(np.float64)
+    want = orc.score(Qs, K, w.scale, share_heads=share)
+    err = np.abs(got - want)
+    # fp32 exponentials and sums of probabilities computed from exact bf16 products
+    assert np.all(err <= 2e-7 + 2e-5 * want), (err.max(), (err / (want + 1e-30)).max())
+    rep = w.Hq // w.Hkv
+    np.testing.assert_allclose(got.sum(1), Qs.shape[1] * rep * (w.Hkv if share else 1), rtol=1e-5)
+    return got, want
+
+
+def test_score_f32_config1():
+    w = synth.config1()
+    _score_check(w, w.Q, w.K)
+
+
+@pytest.mark.parametrize("share", [False, True])
+def test_score_bf16_midsize(share):
+    w = synth.midsize()
+    Qs = w.Q[:, w.score_rows]
+    _score_check(w, Qs, w.K, share=share)
+
+
+@pytest.mark.parametrize("n_qs,nk", [(1, 1), (33, 255), (64, 256), (65, 257), (130, 1300)])
+def test_score_bf16_ragged(n_qs, nk):
+    w = synth.midsize(n_past=1)
+    rng = np.random.default_rng(n_qs + nk)
+    Qs = synth.to_bf16(rng.standard_normal((4, n_qs, 128)).astype(np.float32))
+    K = synth.to_bf16(rng.standard_normal((2, nk, 128)).astype(np.float32))
+    w.Hq, w.Hkv = 4, 2
+    _score_check(w, Qs, K)
+
+
+def test_score_with_supplied_lse_matches_internal_pass():
+    w = synth.midsize()
+    Qs = w.Q[:, w.score_rows]
+    _, L = orc.frame_attn(Qs, w.K, w.V, w.scale)
+    got, _ = _score_check(w, Qs, w.K, lse=dev(L.astype(np.float32), None))
+    assert got.shape == (w.Hkv, w.Nk)
+
+
+def test_score_is_bit_reproducible():
+    w = synth.midsize()
+    Qs, K = dev(w.Q[:, w.score_rows], "bf16"), dev(w.K, "bf16")
+    a = pk.pc_score(Qs, K, w.Nk, w.scale)
+    b = pk.pc_score(Qs, K, w.Nk, w.scale)
+    assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------------------------- select + compact
+def _compact_run(w, sc, budgets, in_place, share=False, hsel=None):
+    dt = w.dtype
+    hsel = (1 if share else w.Hkv) if hsel is None else hsel
+    K, V = dev(w.K, dt), dev(w.V, dt)
+    pos = dev(np.broadcast_to(w.pos_k[None], (hsel, w.Nk, 3)).copy(), None)
+    scd = dev(sc.astype(np.float32), None)
+    plan, nk_out = pk.pc_compact_plan(w.segments, budgets)
+    idx = torch.full((hsel, nk_out), -1, dtype=torch.int32, device=DEV)
+    if in_place:
+        segs, nk = pk.pc_compact(K, V, pos, scd, w.segments, budgets, share_heads=share, idx=idx)
+        Ko, Vo, po = K[:, :nk], V[:, :nk], pos[:, :nk]
+    else:
+        Ko = torch.empty((w.Hkv, nk_out, w.D), dtype=K.dtype, device=DEV)
+        Vo, po = torch.empty_like(Ko), torch.empty((hsel, nk_out, 3), dtype=torch.int32, device=DEV)
+        segs, nk = pk.pc_compact(K, V, pos, scd, w.segments, budgets, share_heads=share, out=(Ko, Vo, po), idx=idx)
+        assert torch.equal(K, dev(w.K, dt))           # out of place leaves the cache alone
+    assert segs == plan and nk == nk_out
+    return host(Ko), host(Vo), host(po), host(idx), segs
+
+
+@pytest.mark.parametrize("in_place", [False, True])
+@pytest.mark.parametrize("case", ["c1", "mid", "mid_f32"])
+def test_compact_matches_oracle_on_given_scores(case, in_place):
+    w = synth.config1() if case == "c1" else synth.midsize(dtype="f32" if case == "mid_f32" else "bf16")
+    rng = np.random.default_rng(3)
+    sc = rng.random((w.Hkv, w.Nk)).astype(np.float32)       # fp32 scores given: selection is exact
+    budgets = budgets_for(w)
+    Kw, Vw, pw, iw, sw = orc.compact(w.K, w.V, np.broadcast_to(w.pos_k[None], (w.Hkv, w.Nk, 3)),
+                                     sc, w.segments, budgets)
+    Kg, Vg, pg, ig, sg = _compact_run(w, sc, budgets, in_place)
+    assert np.array_equal(ig, iw) and sg == sw
+    assert np.array_equal(Kg, Kw.astype(np.float32)) and np.array_equal(Vg, Vw.astype(np.float32))
+    assert np.array_equal(pg, pw)
+
+
+@pytest.mark.parametrize("in_place", [False, True])
+def test_compact_ties_zero_budgets_and_share_heads(in_place):
+    w = synth.midsize(n_past=5)
+    rng = np.random.default_rng(9)
+    sc = (rng.integers(0, 4, (1, w.Nk)) / 4.0).astype(np.float32)   # heavy ties
+    sc[0, w.segments[3][0]:w.segments[3][0] + w.segments[3][1]] = 0.25   # one frame all equal
+    budgets = [s[1] for s in w.segments]
+    budgets[2], budgets[3], budgets[4], budgets[5], budgets[6] = 0, 17, 1, w.n_frame - 1, 64
+    Kw, Vw, pw, iw, sw = orc.compact(w.K, w.V, w.pos_k[None], sc, w.segments, budgets, share_heads=True)
+    Kg, Vg, pg, ig, sg = _compact_run(w, sc, budgets, in_place, share=True)
+    assert np.array_equal(ig, iw) and sg == sw
+    assert np.array_equal(Kg, Kw.astype(np.float32)) and np.array_equal(Vg, Vw.astype(np.float32))
+    assert np.array_equal(pg, pw)
+
+
+def test_compact_long_segment_generic_select_and_negative_zero():
+    # a frame longer than the register-resident limit takes the generic select path
+    rng = np.random.default_rng(21)
+    n = 5000
+    segs = [(0, 8, pk.PC_SEG_TEXT, -1), (8, n, pk.PC_SEG_FRAME, 1), (8 + n, 40, pk.PC_SEG_SELF, 2)]
+    nk = 8 + n + 40
+    sc = rng.random((1, nk)).astype(np.float32)
+    sc[0, 8:8 + 600] = 0.0
+    sc[0, 8:8 + 600:2] = -0.0                                   # -0 ties with +0
+    K = rng.standard_normal((1, nk, 64)).astype(np.float32)
+    V = rng.standard_normal((1, nk, 64)).astype(np.float32)
+    pos = rng.integers(0, 100, (1, nk, 3)).astype(np.int32)
+    budgets = [8, n - 300, 40]
+    Kw, Vw, pw, iw, sw = orc.compact(K, V, pos, sc, segs, budgets)
+    Kd, Vd, pd = dev(K, "f32"), dev(V, "f32"), dev(pos, None)
+    idx = torch.empty((1, sw[-1][0] + sw[-1][1]), dtype=torch.int32, device=DEV)
+    sg, nko = pk.pc_compact(Kd, Vd, pd, dev(sc, None), segs, budgets, idx=idx)
+    assert sg == sw and np.array_equal(host(idx), iw)
+    assert np.array_equal(host(Kd[:, :nko]), Kw) and np.array_equal(host(pd[:, :nko]), pw)
+
+
+def test_in_place_compaction_repeated_random_budgets():
+    # the in-place ordering protocol against the out-of-place result, many budget patterns
+    w = synth.midsize(n_past=9, gh=16, gw=21, n_text=24)
+    rng = np.random.default_rng(100)
+    for trial in range(12):
+        sc = rng.random((w.Hkv, w.Nk)).astype(np.float32)
+        budgets = [s[1] if s[2] != pk.PC_SEG_FRAME else int(rng.integers(0, s[1] + 1)) for s in w.segments]
+        if trial == 0:
+            budgets = [s[1] for s in w.segments]                       # nothing moves
+        if trial == 1:
+            budgets = [s[1] if s[2] != pk.PC_SEG_FRAME else 1 for s in w.segments]
+        a = _compact_run(w, sc, budgets, in_place=False)
+        b = _compact_run(w, sc, budgets, in_place=True)
+        for x, y in zip(a[:4], b[:4]):
+            assert np.array_equal(x, y), f"trial {trial}"
+
+
+# ------------------------------------------------------------------------------- whole path
+def _chain(w, rope):
+    dt = w.dtype
+    Q, K, V = dev(w.Q, dt), dev(w.K, dt), dev(w.V, dt)
+    pos = dev(np.broadcast_to(w.pos_k[None], (w.Hkv, w.Nk, 3)).copy(), None)
+    Qo, Ko = w.Q.astype(np.float64), w.K.astype(np.float64)
+    newest = w.segments[-1]
+    if rope:   # a1: rotate the new frame's queries and the newest cached frame's keys
+        pk.pc_rope3d(Q, dev(w.pos_q, None), w.sections, w.base)
+        kn = K[:, newest[0]:newest[0] + newest[1]]
+        pk.pc_rope3d(kn, dev(w.pos_k[newest[0]:newest[0] + newest[1]], None), w.sections, w.base)
+        rnd = orc.round_to_bf16 if dt == "bf16" else (lambda a: a.astype(np.float32).astype(np.float64))
+        Qo = rnd(orc.rope3d(w.Q, w.pos_q, w.sections, w.base))
+        Ko = Ko.copy()
+        Ko[:, newest[0]:newest[0] + newest[1]] = rnd(orc.rope3d(
+            w.K[:, newest[0]:newest[0] + newest[1]], w.pos_k[newest[0]:newest[0] + newest[1]], w.sections, w.base))
+    # where the device rotation rounded differently from the oracle's, scores legitimately differ
+    q_same = np.array_equal(host(Q).astype(np.float64), Qo)
+    k_diff_rows = np.any(host(K).astype(np.float64) != Ko, axis=2)          # [Hkv][Nk]
+    rows = torch.from_numpy(w.score_rows).to(DEV)
+    Qs = Q[:, rows].contiguous()
+    sc = pk.pc_score(Qs, K, w.Nk, w.scale)                                   # a2
+    budgets = budgets_for(w)                                                # a3
+    idx = torch.empty((w.Hkv, pk.pc_compact_plan(w.segments, budgets)[1]), dtype=torch.int32, device=DEV)
+    segs, nk = pk.pc_compact(K, V, pos, sc, w.segments, budgets, idx=idx)    # a4 + a5, in place
+    O = pk.pc_frame_attn(Q, K, V, nk, w.scale)                               # a6
+    # oracle, step by step
+    sco = orc.score(Qo[:, w.score_rows], Ko, w.scale)
+    Kp, Vp, pp, io, so = orc.compact(Ko, w.V, np.broadcast_to(w.pos_k[None], (w.Hkv, w.Nk, 3)), sco,
+                                     w.segments, budgets)
+    assert segs == so
+    ig = host(idx)
+    # identical inputs: the 1e-6 band.  Keys rotated to a different bf16 are exempt; if any
+    # query element rounded differently every score moves a little and the band is 1e-5.
+    n_ex = check_selection(ig, sco, w.segments, budgets, band=BAND if q_same else 1e-5,
+                           other_input=k_diff_rows if rope else None)
+    assert np.array_equal(host(pos[:, :nk]), np.stack([w.pos_k[ig[h]] for h in range(w.Hkv)]))
+    # attention over the keys the device actually kept (identical to the oracle's set up to
+    # the exempted ties), computed by the oracle in fp64
+    Kk = np.stack([Ko[g][ig[g]] for g in range(w.Hkv)])
+    Vk = np.stack([w.V[g][ig[g]].astype(np.float64) for g in range(w.Hkv)])
+    Ow, _ = orc.frame_attn(Qo, Kk, Vk, w.scale)
+    err = np.abs(host(O).astype(np.float64) - Ow)
+    return err, n_ex, (ig == io).mean()
+
+
+def test_whole_path_config1_fp32():
+    err, n_ex, same = _chain(synth.config1(), rope=False)
+    assert err.max() <= 1e-5
+    assert n_ex == 0 and same == 1.0
+
+
+def test_whole_path_midsize_bf16_with_rope():
+    err, n_ex, same = _chain(synth.midsize(), rope=True)
+    assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
+    assert same > 0.99
+
+
+def test_full_budget_packed_equals_dense_on_device():
+    w = synth.midsize()
+    Q, K, V = dev(w.Q, "bf16"), dev(w.K, "bf16"), dev(w.V, "bf16")
+    O_dense = pk.pc_frame_attn(Q, K, V, w.Nk, w.scale)
+    pos = dev(w.pos_k[None].repeat(w.Hkv, 0), None)
+    sc = pk.pc_score(Q[:, :64].contiguous(), K, w.Nk, w.scale)
+    segs, nk = pk.pc_compact(K, V, pos, sc, w.segments, [s[1] for s in w.segments])
+    assert nk == w.Nk and segs == w.segments
+    assert torch.equal(pk.pc_frame_attn(Q, K, V, nk, w.scale), O_dense)

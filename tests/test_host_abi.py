@@ -1,0 +1,137 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its
+host-side logic (budgets, compaction plan, argument validation) agrees with the oracle.
+No device work is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle as orc
+import paper_2601_04359_amd as pk
+from paper_2601_04359_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.lib_path()):
+        from paper_2601_04359_amd.build import build_library
+        build_library()
+    return binding.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    with open(os.path.join(ROOT, "include", "packcache.h")) as f:
+        header = f.read()
+    names = set(re.findall(r"\b(pc_[a-z0-9_]+)\s*\(", header))
+    assert {"pc_budget", "pc_rope3d", "pc_score", "pc_compact", "pc_frame_attn", "pc_compact_plan",
+            "pc_strerror", "pc_last_error_detail", "pc_version", "pc_score_workspace_bytes",
+            "pc_compact_workspace_bytes", "pc_frame_attn_workspace_bytes"} <= names
+    for n in names:
+        assert hasattr(L, n), n
+    assert pk.pc_version() >= 100
+    assert pk.pc_strerror(0) == "ok" and "NULL" in pk.pc_strerror(-1)
+
+
+@pytest.mark.parametrize("gamma", [0.5, 0.7, 0.85, 0.95, 1.0, 0.3333333333333333, 1e-3])
+@pytest.mark.parametrize("N,n_past,b_min", [(64, 4, 8), (4032, 47, 512), (4032, 23, 0), (4096, 60, 1), (7, 3, 0)])
+def test_budget_pow_matches_oracle(L, gamma, N, n_past, b_min):
+    assert pk.pc_budget(pk.PC_BUDGET_POW, N, n_past, gamma, b_min) == orc.budget_pow(N, n_past, gamma, b_min)
+
+
+def test_budget_pow_config_values(L):
+    assert pk.pc_budget(pk.PC_BUDGET_POW, 64, 4, 0.7, 8) == [44, 31, 21, 15]
+    assert sum(pk.pc_budget(pk.PC_BUDGET_POW, 4032, 47, 0.85, 512)) == 37512
+    assert pk.pc_budget(pk.PC_BUDGET_POW, 4096, 12, 0.5, 0) == [4096 >> d for d in range(1, 13)]
+    assert pk.pc_budget(pk.PC_BUDGET_POW, 100, 0, 0.5, 0) == []
+
+
+@pytest.mark.parametrize("rho", [0.5, 0.7, 0.85, 0.95, 1.0])
+@pytest.mark.parametrize("w", [1, 2, 3, 12, 47])
+@pytest.mark.parametrize("q_min", [0, 100, 512, 3000])
+def test_budget_norm_and_half_match_oracle(L, rho, w, q_min):
+    assert pk.pc_budget(pk.PC_BUDGET_NORM, 4084, w, rho, q_min) == orc.budget_norm(4084, w, rho, q_min)
+    assert pk.pc_budget(pk.PC_BUDGET_HALF, 4084, w, 0.0, q_min) == orc.budget_half(4084, w, q_min)
+    assert pk.pc_budget(pk.PC_BUDGET_SLIDE, 4084, w) == orc.budget_slide(4084, w)
+
+
+def test_budget_half_series_from_the_paper(L):
+    assert pk.pc_budget(pk.PC_BUDGET_HALF, 4096, 4) == [2048, 1024, 512, 512]
+    assert pk.pc_budget(pk.PC_BUDGET_HALF, 4096, 1) == [4096]
+
+
+def test_budget_errors(L):
+    for args in [(9, 10, 2, 0.5, 0), (0, -1, 2, 0.5, 0), (0, 10, -2, 0.5, 0), (0, 10, 2, 0.0, 0),
+                 (0, 10, 2, 1.5, 0), (1, 10, 2, -0.1, 0), (0, 10, 2, 0.5, -1)]:
+        with pytest.raises(pk.PackCacheError) as e:
+            pk.pc_budget(*args)
+        assert e.value.status == -5
+    assert L.pc_budget(0, 10, 2, 0.5, 0, None) == -1
+    assert b"budget_out" in L.pc_last_error_detail()
+
+
+def test_compact_plan_matches_oracle(L):
+    w = synth.config1()
+    b = pk.pc_budget(pk.PC_BUDGET_POW, w.n_frame, w.n_past, w.gamma, w.b_min)
+    budgets = pk.segment_budgets(w.segments, b)
+    assert budgets == [16, 64, 15, 21, 31, 44]
+    segs, nk = pk.pc_compact_plan(w.segments, budgets)
+    assert segs == orc.packed_segments(w.segments, budgets) and nk == 191
+    # budget above the segment length is clamped, zero budget empties the segment
+    segs, nk = pk.pc_compact_plan(w.segments, [0, 0, 1000, 0, 5, 64])
+    assert [s[1] for s in segs] == [16, 64, 64, 0, 5, 64] and nk == 213
+
+
+def test_compact_plan_errors(L):
+    with pytest.raises(pk.PackCacheError) as e:
+        pk.pc_compact_plan([(0, 4, 0, 0), (5, 4, 2, 1)], [4, 4])        # gap in the table
+    assert e.value.status == -2
+    with pytest.raises(pk.PackCacheError) as e:
+        pk.pc_compact_plan([(0, 4, 2, 0)], [-1])
+    assert e.value.status == -5
+    with pytest.raises(pk.PackCacheError) as e:
+        pk.pc_compact_plan([(0, 4, 7, 0)], [1])                          # unknown kind
+    assert e.value.status == -2
+
+
+def test_argument_validation_returns_before_any_device_work(L):
+    one = C.c_void_p(16)   # non-NULL dummy; every call below must fail before touching it
+    # dtype
+    assert L.pc_frame_attn(one, one, one, 5, 2, 1, 4, 4, 128, 512, 512, 512, 0.1, one, None, None, 0, None) == -3
+    # Hq not a multiple of Hkv
+    assert L.pc_frame_attn(one, one, one, 1, 3, 2, 4, 4, 128, 512, 512, 512, 0.1, one, None, None, 0, None) == -2
+    # empty key set
+    assert L.pc_frame_attn(one, one, one, 1, 2, 1, 4, 0, 128, 512, 512, 512, 0.1, one, None, None, 0, None) == -2
+    # NULL tensor
+    assert L.pc_frame_attn(None, one, one, 1, 2, 1, 4, 4, 128, 512, 512, 512, 0.1, one, None, None, 0, None) == -1
+    # bf16 tier is D = 128 only
+    assert L.pc_frame_attn(one, one, one, 1, 2, 1, 4, 4, 64, 256, 256, 256, 0.1, one, None, None, 0, None) == -4
+    # stride too small
+    assert L.pc_frame_attn(one, one, one, 1, 2, 1, 4, 4, 128, 8, 512, 512, 0.1, one, None, None, 0, None) == -2
+    # rope: sections must add up to D
+    assert L.pc_rope3d(one, 1, 1, 4, 128, 512, one, 32, 48, 40, 1e4, None) == -2
+    assert L.pc_rope3d(None, 1, 1, 4, 128, 512, one, 32, 48, 48, 1e4, None) == -1
+    # score: workspace missing / too small
+    need = L.pc_score_workspace_bytes(4, 2, 8, 100, 0)
+    assert need > 0
+    assert L.pc_score(one, one, 1, 4, 2, 8, 100, 128, 1024, 12800, 0.1, None, one, 100, 0, None, 0, None) == -6
+    assert L.pc_score(one, one, 1, 4, 2, 8, 100, 128, 1024, 12800, 0.1, None, one, 100, 0, one, need - 1, None) == -6
+    # compact: too many segments; partial aliasing of outputs
+    seg = (binding.pc_segment * 2)(binding.pc_segment(0, 4, 0, 0), binding.pc_segment(4, 8, 2, 1))
+    bud = (C.c_int32 * 2)(4, 3)
+    assert L.pc_compact(one, one, one, 1, 1, 128, 4096, 0, one, 0, seg, 500, bud, 0, one, one, one, 4096, 0,
+                        None, 0, None, None, one, 1 << 20, None) == -2
+    two = C.c_void_p(4096)
+    assert L.pc_compact(one, one, one, 1, 1, 128, 4096, 36, one, 12, seg, 2, bud, 0, one, two, one, 4096, 36,
+                        None, 0, None, None, one, 1 << 20, None) == -2
+    assert b"alias" in L.pc_last_error_detail()
+
+
+def test_binding_raises_without_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "lib_path", lambda: str(tmp_path / "libpackcache.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.pc_version()
