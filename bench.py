@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the PackCache hot path on one MI355X.
+
+A step is one pass of the whole path over one layer at frame 24 (16 query heads, 4 KV
+heads, D = 128, 4032 tokens per frame, 256 text tokens, 23 past frames):
+    pc_rope3d (new frame's Q, newest cached K) -> pc_score (512 sampled queries) ->
+    pc_budget (gamma 0.85, floor 512) -> pc_compact (select + gather) -> pc_frame_attn.
+Inputs are seeded synthetic tensors already resident in HBM when timing starts.
+Prints ONE JSON line.  `--sweep` adds the per-frame dense-vs-packed table for frames 1..48
+(written to gpurun_out/sweep.json as well).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def attn_flops(hq, nq, nk, d):
+    return 4.0 * hq * nq * nk * d
+
+
+def gather_bytes(rows, hkv, d, elt=2):
+    """Algorithmic bytes of one compaction: every kept row's K and V read and written once,
+    its int32 index read, its (t, h, w) read and written."""
+    return rows * hkv * (2 * 2 * d * elt + 4 + 2 * 12)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--sweep", action="store_true", help="per-frame dense vs packed, frames 1..48")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-f48", action="store_true", help="skip the frame-48 compaction / dense legs")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2601_04359_amd as pk
+    from paper_2601_04359_amd import synth
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    pk.lib()   # fail loudly if the HIP library is missing
+
+    def up(a, bf=True):
+        t = torch.from_numpy(np.ascontiguousarray(a))
+        return (t.to(torch.bfloat16) if bf else t).to(dev)
+
+    def timed(fn, reps):
+        """Mean milliseconds of fn() measured with events on the stream the kernels run on."""
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in ev]))
+
+    # ------------------------------------------------------------------ frame-24 layer
+    w = synth.config2(seed=1000, n_past=23)
+    Hq, Hkv, D, Nq, Nk = w.Hq, w.Hkv, w.D, w.Nq, w.Nk
+    Q0, K, V = up(w.Q), up(w.K), up(w.V)
+    Q = Q0.clone()
+    pos = up(np.broadcast_to(w.pos_k[None], (Hkv, Nk, 3)).copy(), bf=False)
+    pos_q = up(w.pos_q, bf=False)
+    newest = w.segments[-1]
+    pos_new = up(w.pos_k[newest[0]:newest[0] + newest[1]], bf=False)
+    rows = up(w.score_rows.astype(np.int32), bf=False)
+    budgets = pk.segment_budgets(w.segments, pk.pc_budget(pk.PC_BUDGET_POW, w.n_frame, w.n_past, w.gamma, w.b_min))
+    plan, nk_packed = pk.pc_compact_plan(w.segments, budgets)
+    Kp = torch.empty((Hkv, nk_packed, D), dtype=torch.bfloat16, device=dev)
+    Vp = torch.empty_like(Kp)
+    pp = torch.empty((Hkv, nk_packed, 3), dtype=torch.int32, device=dev)
+    O = torch.empty_like(Q)
+    score = torch.empty((Hkv, Nk), dtype=torch.float32, device=dev)
+    ws_s = torch.empty(pk.pc_score_workspace_bytes(Hq, Hkv, rows.numel(), Nk), dtype=torch.uint8, device=dev)
+    ws_c = torch.empty(pk.pc_compact_workspace_bytes(Hkv, Nk), dtype=torch.uint8, device=dev)
+    k_new = K[:, newest[0]:newest[0] + newest[1]]
+    kept_past_rows = nk_packed - (w.n_text + w.n_frame)
+
+    ev_attn = []
+
+    def step(record=False):
+        pk.pc_rope3d(Q, pos_q, w.sections, w.base)
+        pk.pc_rope3d(k_new, pos_new, w.sections, w.base)
+        pk.pc_score(Q, K, Nk, w.scale, score=score, ws=ws_s, q_rows=rows)
+        b = pk.segment_budgets(w.segments, pk.pc_budget(pk.PC_BUDGET_POW, w.n_frame, w.n_past, w.gamma, w.b_min))
+        _, nk = pk.pc_compact(K, V, pos, score, w.segments, b, out=(Kp, Vp, pp), ws=ws_c)
+        if record:
+            a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+        pk.pc_frame_attn(Q, Kp, Vp, nk, w.scale, O=O)
+        if record:
+            e.record()
+            ev_attn.append((a, e))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(record=True)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    attn_ms = float(np.mean([a.elapsed_time(e) for a, e in ev_attn]))
+    fl_packed = attn_flops(Hq, Nq, nk_packed, D)
+    attn_tflops = fl_packed / (attn_ms * 1e-3) / 1e12
+
+    # the other steps of the path, one by one (same stream, events around each call)
+    rope_ms = timed(lambda: (pk.pc_rope3d(Q, pos_q, w.sections, w.base),
+                             pk.pc_rope3d(k_new, pos_new, w.sections, w.base)), 10)
+    score_ms = timed(lambda: pk.pc_score(Q, K, Nk, w.scale, score=score, ws=ws_s, q_rows=rows), 10)
+    compact_ms = timed(lambda: pk.pc_compact(K, V, pos, score, w.segments, budgets, out=(Kp, Vp, pp), ws=ws_c), 10)
+    dense_ms = timed(lambda: pk.pc_frame_attn(Q, K, V, Nk, w.scale, O=O), 3)
+    score_flops = 2.0 * 2.0 * D * rows.numel() * Hq * Nk          # two QK^T passes
+    out = {
+        "metric": "packed frame-attn ms/layer + TFLOP/s (% MFMA peak); compaction GB/s at 48 frames",
+        "value": round(attn_tflops, 2),
+        "unit": "TFLOP/s (packed pc_frame_attn, bf16, frame 24)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "configs[1]: single layer at frame 24", "Hq": Hq, "Hkv": Hkv, "D": D,
+                   "Nq": Nq, "Nk_dense": Nk, "Nk_packed": nk_packed, "gamma": w.gamma, "b_min": w.b_min,
+                   "score_queries": int(rows.numel())},
+        "attn_packed_ms_per_layer": round(attn_ms, 4),
+        "attn_dense_ms_per_layer": round(dense_ms, 4),
+        "attn_dense_tflops": round(attn_flops(Hq, Nq, Nk, D) / (dense_ms * 1e-3) / 1e12, 2),
+        "dense_vs_packed_speedup_f24": round(dense_ms / attn_ms, 3),
+        "dense_vs_packed_path_speedup_f24": round(dense_ms / ms_per_step, 3),
+        "step_breakdown_ms": {"rope3d": round(rope_ms, 4), "score": round(score_ms, 4),
+                              "compact": round(compact_ms, 4), "frame_attn": round(attn_ms, 4)},
+        "score_tflops": round(score_flops / (score_ms * 1e-3) / 1e12, 2),
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": round(attn_tflops, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+    }
+    del Q, Q0, K, V, Kp, Vp, pp, O, score, pos
+
+    # ------------------------------------------------------------------ frame 48: compaction, dense
+    if not args.no_f48 or args.sweep:
+        w48 = synth.config2(seed=1001, n_past=47)
+        Nk48 = w48.Nk
+        K48, V48, Q48 = up(w48.K), up(w48.V), up(w48.Q)
+        pos48 = up(np.broadcast_to(w48.pos_k[None], (Hkv, Nk48, 3)).copy(), bf=False)
+        Kw, Vw, pw = K48.clone(), V48.clone(), pos48.clone()
+        rows48 = up(w48.score_rows.astype(np.int32), bf=False)
+        ws_s48 = torch.empty(pk.pc_score_workspace_bytes(Hq, Hkv, rows48.numel(), Nk48), dtype=torch.uint8, device=dev)
+        ws_c48 = torch.empty(pk.pc_compact_workspace_bytes(Hkv, Nk48), dtype=torch.uint8, device=dev)
+        sc48 = pk.pc_score(Q48, K48, Nk48, w48.scale, ws=ws_s48, q_rows=rows48)
+        O48 = torch.empty_like(Q48)
+        comp = {}
+        for gamma in (0.7, 0.85, 0.95):
+            b48 = pk.segment_budgets(w48.segments, pk.pc_budget(pk.PC_BUDGET_POW, w48.n_frame, 47, gamma, 512))
+            _, nk48p = pk.pc_compact_plan(w48.segments, b48)
+            kept = nk48p - (w48.n_text + w48.n_frame)
+            ts = []
+            for rep in range(6):
+                Kw.copy_(K48), Vw.copy_(V48), pw.copy_(pos48)          # restore the cache (untimed)
+                a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                pk.pc_compact(Kw, Vw, pw, sc48, w48.segments, b48, ws=ws_c48)   # in place
+                e.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(e))
+            ms = float(np.mean(ts[1:]))
+            gb = gather_bytes(kept, Hkv, D) / 1e9
+            comp[str(gamma)] = {"kept_past_rows": kept, "ms_per_layer": round(ms, 4),
+                                "GBps": round(gb / (ms * 1e-3), 1), "frac_hbm": round(gb / (ms * 1e-3) / PEAK_HBM_GBS, 4)}
+            if gamma == 0.85:
+                packed48_ms = timed(lambda: pk.pc_frame_attn(Q48, Kw, Vw, nk48p, w48.scale, O=O48), 3)
+                nk48_packed = nk48p
+        dense48_ms = timed(lambda: pk.pc_frame_attn(Q48, K48, V48, Nk48, w48.scale, O=O48), 2)
+        score48_ms = timed(lambda: pk.pc_score(Q48, K48, Nk48, w48.scale, score=sc48, ws=ws_s48, q_rows=rows48), 3)
+        out["compaction_f48_in_place"] = comp
+        out["roofline_compact"] = {"bound": "hbm", "kernel": "select_kernel + gather_kernel (in place, gamma 0.85)",
+                                   "achieved": comp["0.85"]["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                   "frac": comp["0.85"]["frac_hbm"], "traffic": None}
+        out["frame48"] = {"Nk_dense": Nk48, "Nk_packed": nk48_packed, "attn_dense_ms": round(dense48_ms, 4),
+                          "attn_packed_ms": round(packed48_ms, 4),
+                          "attn_packed_tflops": round(attn_flops(Hq, Nq, nk48_packed, D) / (packed48_ms * 1e-3) / 1e12, 2),
+                          "attn_dense_tflops": round(attn_flops(Hq, Nq, Nk48, D) / (dense48_ms * 1e-3) / 1e12, 2),
+                          "dense_vs_packed_speedup": round(dense48_ms / packed48_ms, 3),
+                          "score_ms": round(score48_ms, 4),
+                          "score_tflops": round(2 * 2.0 * D * rows48.numel() * Hq * Nk48 / (score48_ms * 1e-3) / 1e12, 2)}
+
+        if args.sweep:
+            table = []
+            n_anchor = w48.n_text + w48.n_frame
+            for f in range(1, 49):
+                n_past = f - 1
+                nk_f = n_anchor + w48.n_frame * n_past
+                segs = synth.segment_table(w48.n_text, w48.n_frame, n_past)
+                b = pk.segment_budgets(segs, pk.pc_budget(pk.PC_BUDGET_POW, w48.n_frame, n_past, 0.85, 512))
+                _, nkp = pk.pc_compact_plan(segs, b)
+                d_ms = timed(lambda: pk.pc_frame_attn(Q48, K48, V48, nk_f, w48.scale, O=O48), 2)
+
+                def packed_path():
+                    pk.pc_score(Q48, K48, nk_f, w48.scale, score=sc48, ws=ws_s48, q_rows=rows48)
+                    pk.pc_compact(K48, V48, pos48, sc48, segs, b, out=(Kw, Vw, pw), ws=ws_c48)
+                p_path_ms = timed(packed_path, 2)
+                p_ms = timed(lambda: pk.pc_frame_attn(Q48, Kw, Vw, nkp, w48.scale, O=O48), 2)
+                table.append({"frame": f, "Nk_dense": nk_f, "Nk_packed": nkp, "dense_ms": round(d_ms, 4),
+                              "packed_attn_ms": round(p_ms, 4), "score_compact_ms": round(p_path_ms, 4)})
+            last4 = table[-4:]
+            out["sweep_last4_speedup_attn"] = round(sum(r["dense_ms"] for r in last4) /
+                                                    sum(r["packed_attn_ms"] for r in last4), 3)
+            out["sweep_last4_speedup_path"] = round(
+                sum(r["dense_ms"] for r in last4) /
+                sum(r["packed_attn_ms"] + r["score_compact_ms"] for r in last4), 3)
+            out["sweep_total_speedup_attn"] = round(sum(r["dense_ms"] for r in table) /
+                                                    sum(r["packed_attn_ms"] for r in table), 3)
+            os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+            with open(os.path.join(ROOT, "gpurun_out", "sweep.json"), "w") as fh:
+                json.dump(table, fh, indent=0)
+        del K48, V48, Q48, Kw, Vw
+
+    # ------------------------------------------------------------------ CPU baseline: the oracle
+    if not args.no_cpu:
+        import oracle as orc
+        n_rows = 256
+        rs = np.linspace(0, Nq - 1, n_rows).astype(np.int64)
+        Ks, Vs = w.K[:, :nk_packed], w.V[:, :nk_packed]      # same key count as the packed call
+        t0 = time.perf_counter()
+        orc.frame_attn(w.Q[:, rs], Ks, Vs, w.scale)
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = len(os.sched_getaffinity(0))
+        out["cpu_baseline"] = {"value": round(attn_flops(Hq, n_rows, nk_packed, D) / dt / 1e12, 5),
+                               "unit": "TFLOP/s (fp64 NumPy oracle)", "cores": int(threads), "kind": "oracle",
+                               "seconds": round(dt, 2),
+                               "sample": f"oracle.frame_attn on {n_rows} of {Nq} query rows x {Hq} heads x "
+                                         f"{nk_packed} keys (same per-row work as the packed call)"}
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -111,9 +111,11 @@ int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride_h,
  * (Eq. 2 probabilities, softmax over ALL Nk keys presented), summed over the n_qs scoring
  * queries and over the query heads of its KV group.  The paper only asks for
  * "attention-relevant" tokens (Sec. 3.4); this column mass is the reading built here.
- *   Qs     dev, [Hq][n_qs][D]  scoring queries (already rotated), head stride q_stride_h
+ *   Qs     dev, [Hq][*][D]     queries (already rotated), head stride q_stride_h
+ *   q_rows dev or NULL, int32 [n_qs]: rows of Qs that score (the same for every head),
+ *          e.g. an evenly spread sample of the frame.  NULL: rows 0 .. n_qs-1.
  *   K      dev, [Hkv][Nk][D]   cached keys (already rotated), head stride k_stride_h
- *   lse    dev or NULL, fp32 [Hq][n_qs]: natural-log sum-exp of each query's scaled logits
+ *   lse    dev or NULL, fp32 [Hq][n_qs]: natural-log sum-exp of each scoring query's scaled logits
  *          over the same Nk keys.  NULL: computed here (one extra QK^T pass).
  *   score  dev, fp32 [Hsel][Nk], head stride score_stride_h; Hsel = Hkv, or 1 when
  *          share_heads != 0 (mass summed over the KV heads as well).
@@ -123,8 +125,8 @@ int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride_h,
  */
 size_t pc_score_workspace_bytes(int Hq, int Hkv, int n_qs, int Nk, int share_heads);
 int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hkv, int n_qs, int Nk,
-             int D, int64_t q_stride_h, int64_t k_stride_h, float scale, const float* lse,
-             float* score, int64_t score_stride_h, int share_heads, void* ws,
+             int D, int64_t q_stride_h, int64_t k_stride_h, const int32_t* q_rows, float scale,
+             const float* lse, float* score, int64_t score_stride_h, int share_heads, void* ws,
              size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------

@@ -191,14 +191,20 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   }
 
   if constexpr (kInPlace) {
-    // publish "my sources are in registers", then wait for every lower chunk of this head
-    // whose sources may lie in [r0, r1).  Source row of the i-th kept row of a segment is
-    // bounded by start + i <= src <= start + (len - keep) + i.
-    __threadfence();
+    // Publish "my sources are in registers", then wait for every lower chunk of this head
+    // whose sources may lie in [r0, r1).  Only the ORDER of my stores after their loads
+    // matters (nobody reads what another work-group wrote), so no cache maintenance is
+    // needed: each thread pins its loaded registers (which makes the compiler wait for the
+    // loads), the work-group barrier collects all threads, and relaxed device-scope
+    // accesses carry the flag.
+#pragma unroll
+    for (int it = 0; it < kMaxItems; ++it) asm volatile("" : "+v"(val[it]));
+    asm volatile("" : "+v"(pval));
     __syncthreads();
     int32_t* flags_h = flags + h * chunks_per_head;
     if (threadIdx.x == 0)
-      __hip_atomic_store(&flags_h[cc], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&flags_h[cc], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // Source row of the i-th kept row of a segment: start + i <= src <= start + (len - keep) + i.
     int row_lo = INT_MAX, row_hi = -1;
     for (int s = 0; s < tab.n; ++s) {
       const int a = tab.start[s], b = a + tab.len[s];
@@ -214,7 +220,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
       const int c_lo = row_lo / kGatherRows, c_hi = min(row_hi / kGatherRows, cc - 1);
       for (int c = c_lo + threadIdx.x; c <= c_hi; c += kGatherThreads) {
         int spins = 0;
-        while (__hip_atomic_load(&flags_h[c], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == 0) {
+        while (__hip_atomic_load(&flags_h[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
           if (__hip_atomic_load(&sync->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
           if (++spins > kSpinLimit) {  // cannot happen (lower tickets never wait to load); never hang
             __hip_atomic_store(&sync->abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -31,8 +31,8 @@ constexpr int kRowBN = 64;
 constexpr int kRowBM = 256;
 
 __global__ __launch_bounds__(kThreads, 1) void score_rowpass_bf16(
-    const uint16_t* __restrict__ Qs, const uint16_t* __restrict__ K, float2* __restrict__ part,
-    int Hq, int rep, int n_qs, int Nk, int64_t q_stride_h, int64_t k_stride_h, float c,
+    const uint16_t* __restrict__ Qs, const int32_t* __restrict__ q_rows,
+    const uint16_t* __restrict__ K, float2* __restrict__ part, int Hq, int rep, int n_qs, int Nk, int64_t q_stride_h, int64_t k_stride_h, float c,
     int n_row_tiles, int n_splits) {
   __shared__ __align__(16) uint16_t ks[2][kRowBN * kKStride];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -48,7 +48,8 @@ __global__ __launch_bounds__(kThreads, 1) void score_rowpass_bf16(
   bf16x8 qf[2][8];
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb) {
-    const int row = min(row0 + qb * 32 + l32, n_qs - 1);
+    int row = min(row0 + qb * 32 + l32, n_qs - 1);
+    if (q_rows) row = q_rows[row];
 #pragma unroll
     for (int s = 0; s < 8; ++s)
       qf[qb][s] = *reinterpret_cast<const bf16x8*>(Qh + static_cast<int64_t>(row) * kD + s * 16 + g * 8);
@@ -161,8 +162,8 @@ constexpr int kColKeys = 256;
 constexpr size_t kColSmem = kColKeys * kKStride * sizeof(uint16_t) + 4 * kColKeys * sizeof(float);
 
 __global__ __launch_bounds__(kThreads, 2) void score_colpass_bf16(
-    const uint16_t* __restrict__ Qs, const uint16_t* __restrict__ K, const float* __restrict__ lse,
-    float lse_mul, float* __restrict__ score, int64_t score_stride_h, int rep, int n_qs, int Nk,
+    const uint16_t* __restrict__ Qs, const int32_t* __restrict__ q_rows,
+    const uint16_t* __restrict__ K, const float* __restrict__ lse, float lse_mul, float* __restrict__ score, int64_t score_stride_h, int rep, int n_qs, int Nk,
     int64_t q_stride_h, int64_t k_stride_h, float c) {
   extern __shared__ __align__(16) uint8_t smem_raw[];
   uint16_t* ks = reinterpret_cast<uint16_t*>(smem_raw);
@@ -199,7 +200,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_colpass_bf16(
     float lq[2][16];
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
-      const int row = min(row0 + qb * 32 + l32, n_qs - 1);
+      int row = min(row0 + qb * 32 + l32, n_qs - 1);
+      if (q_rows) row = q_rows[row];
 #pragma unroll
       for (int s = 0; s < 8; ++s)
         qf[qb][s] = *reinterpret_cast<const bf16x8*>(Qh + static_cast<int64_t>(row) * kD + s * 16 + g * 8);
@@ -261,6 +263,7 @@ constexpr int kF32Tile = 16;
 
 template <int D>
 __global__ __launch_bounds__(64) void score_rowpass_f32(const float* __restrict__ Qs,
+                                                        const int32_t* __restrict__ q_rows,
                                                         const float* __restrict__ K,
                                                         float* __restrict__ lse, int rep, int n_qs,
                                                         int Nk, int64_t q_stride_h,
@@ -268,7 +271,9 @@ __global__ __launch_bounds__(64) void score_rowpass_f32(const float* __restrict_
   __shared__ float ks[kF32Tile][D];
   const int h = blockIdx.y, kvh = h / rep;
   const int row = blockIdx.x * 64 + threadIdx.x;
-  const float* qrow = Qs + h * q_stride_h + static_cast<int64_t>(min(row, n_qs - 1)) * D;
+  int qr = min(row, n_qs - 1);
+  if (q_rows) qr = q_rows[qr];
+  const float* qrow = Qs + h * q_stride_h + static_cast<int64_t>(qr) * D;
   float q[D];
 #pragma unroll
   for (int d = 0; d < D; ++d) q[d] = qrow[d];
@@ -302,6 +307,7 @@ __global__ __launch_bounds__(64) void score_rowpass_f32(const float* __restrict_
 
 template <int D>
 __global__ __launch_bounds__(64) void score_colpass_f32(const float* __restrict__ Qs,
+                                                        const int32_t* __restrict__ q_rows,
                                                         const float* __restrict__ K,
                                                         const float* __restrict__ lse,
                                                         float* __restrict__ score,
@@ -323,7 +329,10 @@ __global__ __launch_bounds__(64) void score_colpass_f32(const float* __restrict_
     for (int r0 = 0; r0 < n_qs; r0 += kF32Tile) {
       const int nt = min(kF32Tile, n_qs - r0);
       __syncthreads();
-      for (int e = threadIdx.x; e < nt * D; e += 64) qs[e / D][e % D] = Qh[static_cast<int64_t>(r0) * D + e];
+      for (int e = threadIdx.x; e < nt * D; e += 64) {
+        const int qr = q_rows ? q_rows[r0 + e / D] : r0 + e / D;
+        qs[e / D][e % D] = Qh[static_cast<int64_t>(qr) * D + e % D];
+      }
       if (threadIdx.x < nt) ls[threadIdx.x] = lse[static_cast<int64_t>(h) * n_qs + r0 + threadIdx.x];
       __syncthreads();
       for (int j = 0; j < nt; ++j) {
@@ -365,8 +374,8 @@ extern "C" size_t pc_score_workspace_bytes(int Hq, int Hkv, int n_qs, int Nk, in
 }
 
 extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hkv, int n_qs,
-                        int Nk, int D, int64_t q_stride_h, int64_t k_stride_h, float scale,
-                        const float* lse, float* score, int64_t score_stride_h, int share_heads,
+                        int Nk, int D, int64_t q_stride_h, int64_t k_stride_h,
+                        const int32_t* q_rows, float scale, const float* lse, float* score, int64_t score_stride_h, int share_heads,
                         void* ws, size_t ws_bytes, void* stream) {
   PC_REQUIRE(dtype == PC_F32 || dtype == PC_BF16, PC_ERR_DTYPE, "pc_score: dtype %d", dtype);
   PC_REQUIRE(Hq > 0 && Hkv > 0 && Hq % Hkv == 0, PC_ERR_SHAPE,
@@ -374,7 +383,8 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
   PC_REQUIRE(n_qs >= 1 && Nk >= 1, PC_ERR_SHAPE, "pc_score: n_qs=%d Nk=%d must be >= 1", n_qs, Nk);
   PC_REQUIRE(scale > 0.f && isfinite(scale), PC_ERR_SHAPE, "pc_score: scale %g must be > 0", scale);
   PC_REQUIRE(Qs && K && score, PC_ERR_NULL, "pc_score: Qs, K or score is NULL");
-  PC_REQUIRE(q_stride_h >= static_cast<int64_t>(n_qs) * D && k_stride_h >= static_cast<int64_t>(Nk) * D,
+  PC_REQUIRE((q_rows != nullptr || q_stride_h >= static_cast<int64_t>(n_qs) * D || Hq == 1) &&
+                 (k_stride_h >= static_cast<int64_t>(Nk) * D || Hkv == 1),
              PC_ERR_SHAPE, "pc_score: a head stride is smaller than rows*D");
   PC_REQUIRE(share_heads || Hkv == 1 || score_stride_h >= Nk, PC_ERR_SHAPE,
              "pc_score: score head stride %lld < Nk", static_cast<long long>(score_stride_h));
@@ -404,7 +414,7 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
       int n_splits = ceil_div(1024, n_row_tiles * Hq);
       n_splits = std::max(1, std::min(std::min(n_splits, kMaxSplits), n_tiles));
       score_rowpass_bf16<<<dim3(n_row_tiles * Hq, n_splits), kThreads, 0, s>>>(
-          static_cast<const uint16_t*>(Qs), static_cast<const uint16_t*>(K), ws_part, Hq, rep, n_qs, Nk,
+          static_cast<const uint16_t*>(Qs), q_rows, static_cast<const uint16_t*>(K), ws_part, Hq, rep, n_qs, Nk,
           q_stride_h, k_stride_h, c, n_row_tiles, n_splits);
       PC_CHECK_LAUNCH("pc_score row pass");
       const int n_rows = Hq * n_qs;
@@ -422,7 +432,7 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
       attr_set = true;
     }
     score_colpass_bf16<<<dim3(ceil_div(Nk, kColKeys), Hkv), kThreads, kColSmem, s>>>(
-        static_cast<const uint16_t*>(Qs), static_cast<const uint16_t*>(K), lse_in, lse_mul, per_head,
+        static_cast<const uint16_t*>(Qs), q_rows, static_cast<const uint16_t*>(K), lse_in, lse_mul, per_head,
         per_head_stride, rep, n_qs, Nk, q_stride_h, k_stride_h, c);
     PC_CHECK_LAUNCH("pc_score column pass");
   } else {
@@ -433,18 +443,18 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
     if (lse == nullptr) {
       const dim3 grid(ceil_div(n_qs, 64), Hq);
       if (D == 64)
-        score_rowpass_f32<64><<<grid, 64, 0, s>>>(q, k, ws_lse, rep, n_qs, Nk, q_stride_h, k_stride_h, scale);
+        score_rowpass_f32<64><<<grid, 64, 0, s>>>(q, q_rows, k, ws_lse, rep, n_qs, Nk, q_stride_h, k_stride_h, scale);
       else
-        score_rowpass_f32<128><<<grid, 64, 0, s>>>(q, k, ws_lse, rep, n_qs, Nk, q_stride_h, k_stride_h, scale);
+        score_rowpass_f32<128><<<grid, 64, 0, s>>>(q, q_rows, k, ws_lse, rep, n_qs, Nk, q_stride_h, k_stride_h, scale);
       PC_CHECK_LAUNCH("pc_score row pass");
       lse_in = ws_lse;
     }
     const dim3 grid(ceil_div(Nk, 64), Hkv);
     if (D == 64)
-      score_colpass_f32<64><<<grid, 64, 0, s>>>(q, k, lse_in, per_head, per_head_stride, rep, n_qs, Nk,
+      score_colpass_f32<64><<<grid, 64, 0, s>>>(q, q_rows, k, lse_in, per_head, per_head_stride, rep, n_qs, Nk,
                                                   q_stride_h, k_stride_h, scale);
     else
-      score_colpass_f32<128><<<grid, 64, 0, s>>>(q, k, lse_in, per_head, per_head_stride, rep, n_qs, Nk,
+      score_colpass_f32<128><<<grid, 64, 0, s>>>(q, q_rows, k, lse_in, per_head, per_head_stride, rep, n_qs, Nk,
                                                    q_stride_h, k_stride_h, scale);
     PC_CHECK_LAUNCH("pc_score column pass");
   }

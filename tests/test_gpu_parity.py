@@ -222,6 +222,18 @@ def test_score_with_supplied_lse_matches_internal_pass():
     assert got.shape == (w.Hkv, w.Nk)
 
 
+def test_score_row_index_equals_gathered_rows():
+    # scoring rows picked through q_rows must give the same bits as scoring a gathered copy
+    for w in (synth.midsize(), synth.config1()):
+        rows = w.score_rows[::2].astype(np.int32)
+        Q, K = dev(w.Q, w.dtype), dev(w.K, w.dtype)
+        a = pk.pc_score(Q, K, w.Nk, w.scale, q_rows=dev(rows, None))
+        b = pk.pc_score(dev(w.Q[:, rows], w.dtype), K, w.Nk, w.scale)
+        assert torch.equal(a, b)
+        want = orc.score(w.Q[:, rows], w.K, w.scale)
+        assert np.all(np.abs(host(a) - want) <= 2e-7 + 2e-5 * want)
+
+
 def test_score_is_bit_reproducible():
     w = synth.midsize()
     Qs, K = dev(w.Q[:, w.score_rows], "bf16"), dev(w.K, "bf16")
@@ -338,9 +350,8 @@ def _chain(w, rope):
     # where the device rotation rounded differently from the oracle's, scores legitimately differ
     q_same = np.array_equal(host(Q).astype(np.float64), Qo)
     k_diff_rows = np.any(host(K).astype(np.float64) != Ko, axis=2)          # [Hkv][Nk]
-    rows = torch.from_numpy(w.score_rows).to(DEV)
-    Qs = Q[:, rows].contiguous()
-    sc = pk.pc_score(Qs, K, w.Nk, w.scale)                                   # a2
+    rows = dev(w.score_rows.astype(np.int32), None)
+    sc = pk.pc_score(Q, K, w.Nk, w.scale, q_rows=rows)                       # a2
     budgets = budgets_for(w)                                                # a3
     idx = torch.empty((w.Hkv, pk.pc_compact_plan(w.segments, budgets)[1]), dtype=torch.int32, device=DEV)
     segs, nk = pk.pc_compact(K, V, pos, sc, w.segments, budgets, idx=idx)    # a4 + a5, in place
