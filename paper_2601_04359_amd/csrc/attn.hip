@@ -41,223 +41,252 @@ __device__ __forceinline__ int vt_slot(int o) {
   return (o & ~12) | ((o & 4) << 1) | ((o & 8) >> 1);
 }
 
-struct TileRegs {
-  u32x4 k[4];
-  u32x4 v[4];
-};
+// ------------------------------------------------------------------------------------------
+// Ping-pong kernel: 8 waves, two per SIMD, 32 query rows each.  The two waves of a SIMD
+// are kept half an iteration apart by the work-group barrier: while one group of four
+// waves is in its MFMA phase (O^T += V^T P^T of the previous tile, then S^T = K Q^T of
+// the current one) the other is in its VALU phase (softmax of its current tile, staging
+// of the next tile into LDS), so the matrix pipe and the vector ALU overlap.
+// Group 0 stages K, group 1 stages V.  LDS buffers alternate per tile.
+// ------------------------------------------------------------------------------------------
+constexpr int kPPThreads = 512;
+constexpr float kLazyRescale = 8.f;  // base-2 exponent range allowed before re-referencing
 
-__device__ __forceinline__ void load_tile(TileRegs& r, const uint16_t* __restrict__ Kh,
-                                          const uint16_t* __restrict__ Vh, int k0, int Nk) {
-  const int t = threadIdx.x;
-  // K: 16 threads cover one 256-byte row
-  const int kc = t & 15, kr = t >> 4;
+// One MFMA phase of the ping-pong kernel: the 16 products of O^T += V^T P^T (key step
+// i/4, output block i%4) interleaved one-for-one with the 16 of S^T = K Q^T (contraction
+// step i/2, key block i%2), which gives six independent accumulator chains.  LDS fragment
+// reads run kRing products ahead of their use so the matrix pipe does not wait on LDS.
+__device__ __forceinline__ void pp_mfma_phase(const uint16_t* __restrict__ vt_lane,
+                                              const uint16_t* __restrict__ ks_lane, f32x16 (&o)[4],
+                                              f32x16 (&acc)[2], const bf16x8 (&pf)[4],
+                                              const bf16x8 (&qf)[8]) {
+  constexpr int kRing = 6;
+  auto frag = [&](int k) -> bf16x8 {
+    const int i = k >> 1;
+    if ((k & 1) == 0)
+      return *reinterpret_cast<const bf16x8*>(vt_lane + (i & 3) * 32 * kVStride + (i >> 2) * 16);
+    return *reinterpret_cast<const bf16x8*>(ks_lane + (i & 1) * 32 * kKStride + (i >> 1) * 16);
+  };
+  bf16x8 ring[kRing];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int key = min(k0 + kr + 16 * i, Nk - 1);
-    r.k[i] = *reinterpret_cast<const u32x4*>(Kh + static_cast<int64_t>(key) * kD + kc * 8);
-  }
-  // V: a thread takes 4 consecutive keys x 8 dims
-  const int lane = t & 63, wave = t >> 6;
-  const int kg = lane & 15, dc = wave * 4 + (lane >> 4);
+  for (int r = 0; r < kRing; ++r) ring[r] = frag(r);
+  f32x16 zero;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int key = min(k0 + kg * 4 + j, Nk - 1);
-    r.v[j] = *reinterpret_cast<const u32x4*>(Vh + static_cast<int64_t>(key) * kD + dc * 8);
-  }
-}
-
-__device__ __forceinline__ void store_tile(const TileRegs& r, uint16_t* ks, uint16_t* vt) {
-  const int t = threadIdx.x;
-  const int kc = t & 15, kr = t >> 4;
+  for (int i = 0; i < 16; ++i) zero[i] = 0.f;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-    *reinterpret_cast<u32x4*>(ks + (kr + 16 * i) * kKStride + kc * 8) = r.k[i];
-  const int lane = t & 63, wave = t >> 6;
-  const int kg = lane & 15, dc = wave * 4 + (lane >> 4);
-  const int o = kg * 4;
-  const int slot = (o & ~15) | vt_slot(o & 15);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int w = e >> 1;
-    u32x2 out;
-    if (e & 1) {
-      out[0] = (r.v[0][w] >> 16) | (r.v[1][w] & 0xFFFF0000u);
-      out[1] = (r.v[2][w] >> 16) | (r.v[3][w] & 0xFFFF0000u);
+  for (int k = 0; k < 32; ++k) {
+    const int r = k % kRing, i = k >> 1;
+    if ((k & 1) == 0) {
+      o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[r], pf[i >> 2], o[i & 3], 0, 0, 0);
     } else {
-      out[0] = (r.v[0][w] & 0xFFFFu) | (r.v[1][w] << 16);
-      out[1] = (r.v[2][w] & 0xFFFFu) | (r.v[3][w] << 16);
+      const int st = i >> 1, kb = i & 1;
+      acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[r], qf[st], st == 0 ? zero : acc[kb], 0, 0, 0);
     }
-    *reinterpret_cast<u32x2*>(vt + (dc * 8 + e) * kVStride + slot) = out;
+    if (k + kRing < 32) ring[r] = frag(k + kRing);
   }
+  // pin the issue order: kRing LDS reads up front, then one read behind every product
+  __builtin_amdgcn_sched_group_barrier(0x100, kRing, 0);
+#pragma unroll
+  for (int k = 0; k < 32 - kRing; ++k) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(0x008, kRing, 0);
 }
 
-__global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(
+__global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_pp_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     uint16_t* __restrict__ O, float* __restrict__ lse, int rep, int Nq, int Nk, int64_t q_stride_h,
-    int64_t kv_stride_h, int64_t o_stride_h, float c, int n_tiles_q) {
+    int64_t kv_stride_h, int64_t o_stride_h, float c, int n_tiles_q, int group_shift) {
   extern __shared__ __align__(16) uint8_t smem_raw[];
   uint16_t* ks_base = reinterpret_cast<uint16_t*>(smem_raw);
   uint16_t* vt_base = ks_base + 2 * kKTile;
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
   const int l32 = lane & 31, g = lane >> 5;
-  // logical order (head, query tile): heads of one KV group are adjacent, and the
-  // XCD-contiguous mapping keeps a KV group's work-groups on as few L2s as possible.
+  // the two waves that share a SIMD must land in different groups
+  const int group = group_shift ? (wave >> 2) : (wave & 1);
+  const int wsub = group_shift ? (wave & 3) : (wave >> 1);
   const int L = xcd_contiguous_index(blockIdx.x, gridDim.x);
   const int h = L / n_tiles_q, tile = L % n_tiles_q;
   const int kvh = h / rep;
-  const int row0 = tile * kBM + wave * kRowsPerWave;
+  const int row0 = tile * kBM + wave * 32;
   const bool active = row0 < Nq;  // wave-uniform
 
   const uint16_t* Qh = Q + h * q_stride_h;
   const uint16_t* Kh = K + kvh * kv_stride_h;
   const uint16_t* Vh = V + kvh * kv_stride_h;
 
-  // Q fragments (B operand of S^T = K Q^T): lane holds row l32 of each 32-row block,
-  // dims s*16 + g*8 .. +8 of every 16-wide contraction step.
-  bf16x8 qf[2][8];
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const int row = min(row0 + qb * 32 + l32, Nq - 1);
+  bf16x8 qf[8];
+  {
+    const int row = min(row0 + l32, Nq - 1);
 #pragma unroll
     for (int s = 0; s < 8; ++s)
-      qf[qb][s] = *reinterpret_cast<const bf16x8*>(Qh + static_cast<int64_t>(row) * kD + s * 16 + g * 8);
+      qf[s] = *reinterpret_cast<const bf16x8*>(Qh + static_cast<int64_t>(row) * kD + s * 16 + g * 8);
   }
-
-  f32x16 o[4][2];
+  f32x16 o[4];
 #pragma unroll
   for (int db = 0; db < 4; ++db)
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+  f32x16 acc[2];
+  bf16x8 pf[4];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) o[db][qb][i] = 0.f;
-  float m_run[2] = {-INFINITY, -INFINITY};  // running max of c * logit, per lane's query
-  float l_run[2] = {0.f, 0.f};              // this lane's share of the running sum
+  for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pf[k4][e] = static_cast<__bf16>(0.f);
+  float m_ref = -INFINITY, l_run = 0.f;
+  // V^T buffer 1 is read (against zero probabilities) before its first tile arrives
+  for (int e = threadIdx.x; e < kVTile / 8; e += kPPThreads)
+    reinterpret_cast<u32x4*>(vt_base + kVTile)[e] = u32x4{0u, 0u, 0u, 0u};
 
-  const int n_tiles = (Nk + kBN - 1) / kBN;
-  TileRegs regs;
-  load_tile(regs, Kh, Vh, 0, Nk);
-  store_tile(regs, ks_base, vt_base);
+  // staging roles: group 0 moves K rows, group 1 moves (and transposes) V
+  const int t256 = wsub * 64 + lane;
+  const int kc = t256 & 15, kr = t256 >> 4;
+  const int kg = lane & 15, dc = wsub * 4 + (lane >> 4);
+  const int vslot = ((kg * 4) & ~15) | vt_slot((kg * 4) & 15);
+  // Two register sets: tile t travels in set t & 1, loaded two tiles ahead of its LDS store.
+  u32x4 pre0[4], pre1[4];
+  auto stage_load = [&](u32x4 (&pre)[4], int t) {
+    const int k0 = t * kBN;
+    if (group == 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = min(k0 + kr + 16 * i, Nk - 1);
+        pre[i] = *reinterpret_cast<const u32x4*>(Kh + static_cast<int64_t>(key) * kD + kc * 8);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int key = min(k0 + kg * 4 + j, Nk - 1);
+        pre[j] = *reinterpret_cast<const u32x4*>(Vh + static_cast<int64_t>(key) * kD + dc * 8);
+      }
+    }
+  };
+  auto stage_store = [&](const u32x4 (&pre)[4], int t) {
+    const int buf = t & 1;
+    if (group == 0) {
+      uint16_t* ks = ks_base + buf * kKTile;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<u32x4*>(ks + (kr + 16 * i) * kKStride + kc * 8) = pre[i];
+    } else {
+      uint16_t* vt = vt_base + buf * kVTile;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int w = e >> 1;
+        u32x2 out;
+        if (e & 1) {
+          out[0] = (pre[0][w] >> 16) | (pre[1][w] & 0xFFFF0000u);
+          out[1] = (pre[2][w] >> 16) | (pre[3][w] & 0xFFFF0000u);
+        } else {
+          out[0] = (pre[0][w] & 0xFFFFu) | (pre[1][w] << 16);
+          out[1] = (pre[2][w] & 0xFFFFu) | (pre[3][w] << 16);
+        }
+        *reinterpret_cast<u32x2*>(vt + (dc * 8 + e) * kVStride + vslot) = out;
+      }
+    }
+  };
+
+  const int n = (Nk + kBN - 1) / kBN;
+  stage_load(pre0, 0);
+  if (n > 1) stage_load(pre1, 1);
+  if (group == 0) {
+    stage_store(pre0, 0);
+    if (n > 2) stage_load(pre0, 2);
+  }
   __syncthreads();
 
-  for (int j = 0; j < n_tiles; ++j) {
-    const int buf = j & 1;
-    const uint16_t* ks = ks_base + buf * kKTile;
-    const uint16_t* vt = vt_base + buf * kVTile;
-    const bool more = j + 1 < n_tiles;
-    if (more) load_tile(regs, Kh, Vh, (j + 1) * kBN, Nk);
-
-    if (active) {
-      // ---- S^T = K Q^T -----------------------------------------------------------------
-      f32x16 acc[2][2];
+  for (int p = 0; p < 2 * n + 2; ++p) {
+    const int j = (p - group) >> 1;  // tile this group works on (-1 / n: nothing to compute)
+    if (((p + group) & 1) == 0) {
+      // ---------------- MFMA phase: PV of tile j-1, then S of tile j ----------------
+      if (active) {
+        __builtin_amdgcn_s_setprio(1);
+        const uint16_t* vt_lane = vt_base + ((j - 1) & 1) * kVTile + l32 * kVStride + g * 8;
+        const uint16_t* ks_lane = ks_base + (j & 1) * kKTile + l32 * kKStride + g * 8;
+        // Always both products: at j = 0 the P fragments are zero and the V^T buffer was
+        // zero-filled, at j = n the scores computed from a stale K buffer are never used.
+        pp_mfma_phase(vt_lane, ks_lane, o, acc, pf, qf);
+        __builtin_amdgcn_s_setprio(0);
+      }
+    } else {
+      // ---------------- VALU phase: softmax of tile j, stage tile j+1 ----------------
+      if (active && j >= 0 && j < n) {
+        const int k0 = j * kBN;
+        if (k0 + kBN > Nk) {
+          const int lim = Nk - k0 - g * 4;  // first invalid key offset, seen from this lane
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+          for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acc[kb][qb][i] = 0.f;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          const bf16x8 kf =
-              *reinterpret_cast<const bf16x8*>(ks + (kb * 32 + l32) * kKStride + s * 16 + g * 8);
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb)
-            acc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][s], acc[kb][qb], 0, 0, 0);
+            for (int i = 0; i < 16; ++i)
+              if (kb * 32 + (i >> 2) * 8 + (i & 3) >= lim) acc[kb][i] = -INFINITY;
         }
-      }
-      // keys past the end of the cache (last tile only) get probability zero
-      const int k0 = j * kBN;
-      if (k0 + kBN > Nk) {
+        float mx = acc[0][0];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key = k0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-            if (key >= Nk) {
-              acc[kb][0][i] = -INFINITY;
-              acc[kb][1][i] = -INFINITY;
-            }
-          }
-      }
-      // ---- online softmax (per lane: one query per 32-row block) ---------------------
-      bf16x8 pf[2][4];
+          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[kb][i]);
+        mx = fmaxf(mx, wave_half_swap(mx)) * c;
+        if (__any(mx > m_ref + kLazyRescale)) {
+          const float m_new = mx > m_ref + kLazyRescale ? mx : m_ref;
+          const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+          l_run *= alpha;
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        float mx = acc[0][qb][0];
+          for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[kb][qb][i]);
-        mx = fmaxf(mx, wave_half_swap(mx));
-        const float m_new = fmaxf(m_run[qb], mx * c);
-        const float alpha = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+            for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+          m_ref = m_new;
+        }
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
-          float p[16];
+          float pv[16];
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            p[i] = __builtin_amdgcn_exp2f(fmaf(acc[kb][qb][i], c, -m_new));
-            psum += p[i];
+            pv[i] = __builtin_amdgcn_exp2f(fmaf(acc[kb][i], c, -m_ref));
+            psum += pv[i];
           }
 #pragma unroll
           for (int half = 0; half < 2; ++half) {
             bf16x8 f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) f[e] = static_cast<__bf16>(p[half * 8 + e]);
-            pf[qb][kb * 2 + half] = f;
+            for (int e = 0; e < 8; ++e) f[e] = static_cast<__bf16>(pv[half * 8 + e]);
+            pf[kb * 2 + half] = f;
           }
         }
-        l_run[qb] = l_run[qb] * alpha + psum;
-        if (__any(m_new != m_run[qb])) {
-#pragma unroll
-          for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[db][qb][i] *= alpha;
-        }
-        m_run[qb] = m_new;
+        l_run += psum;
       }
-      // ---- O^T += V^T P^T ----------------------------------------------------------------
-#pragma unroll
-      for (int ks16 = 0; ks16 < 4; ++ks16) {
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const bf16x8 vf =
-              *reinterpret_cast<const bf16x8*>(vt + (db * 32 + l32) * kVStride + ks16 * 16 + g * 8);
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb)
-            o[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qb][ks16], o[db][qb], 0, 0, 0);
-        }
+      const int t = j + 1;
+      if (t & 1) {
+        if (t < n) stage_store(pre1, t);
+        if (t + 2 < n) stage_load(pre1, t + 2);
+      } else {
+        if (t < n) stage_store(pre0, t);
+        if (t + 2 < n) stage_load(pre0, t + 2);
       }
     }
-
-    if (more) store_tile(regs, ks_base + (buf ^ 1) * kKTile, vt_base + (buf ^ 1) * kVTile);
     __syncthreads();
   }
 
   if (!active) return;
-  // ---- normalise and store: lane holds O^T[d = db*32 + a*8 + g*4 + b][query l32] ---------
+  const float l_tot = l_run + wave_half_swap(l_run);
+  const float inv = 1.f / l_tot;
+  const int row = row0 + l32;
+  if (row < Nq) {
+    uint16_t* orow = O + h * o_stride_h + static_cast<int64_t>(row) * kD;
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const float l_tot = l_run[qb] + wave_half_swap(l_run[qb]);
-    const float inv = 1.f / l_tot;
-    const int row = row0 + qb * 32 + l32;
-    if (row < Nq) {
-      uint16_t* orow = O + h * o_stride_h + static_cast<int64_t>(row) * kD;
+    for (int db = 0; db < 4; ++db)
 #pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-          u32x2 out;
-          out[0] = pack_bf16x2(o[db][qb][a * 4 + 0] * inv, o[db][qb][a * 4 + 1] * inv);
-          out[1] = pack_bf16x2(o[db][qb][a * 4 + 2] * inv, o[db][qb][a * 4 + 3] * inv);
-          *reinterpret_cast<u32x2*>(orow + db * 32 + a * 8 + g * 4) = out;
-        }
-      if (lse != nullptr && g == 0)
-        lse[static_cast<int64_t>(h) * Nq + row] = (m_run[qb] + log2f(l_tot)) * 0.6931471805599453f;
-    }
+      for (int a = 0; a < 4; ++a) {
+        u32x2 out;
+        out[0] = pack_bf16x2(o[db][a * 4 + 0] * inv, o[db][a * 4 + 1] * inv);
+        out[1] = pack_bf16x2(o[db][a * 4 + 2] * inv, o[db][a * 4 + 3] * inv);
+        *reinterpret_cast<u32x2*>(orow + db * 32 + a * 8 + g * 4) = out;
+      }
+    if (lse != nullptr && g == 0)
+      lse[static_cast<int64_t>(h) * Nq + row] = (m_ref + log2f(l_tot)) * 0.6931471805599453f;
   }
 }
 
@@ -363,7 +392,7 @@ extern "C" int pc_frame_attn(const void* Q, const void* K, const void* V, int dt
                PC_ERR_SHAPE, "pc_frame_attn: bf16 tensors and head strides must be 16-byte aligned");
     static bool attr_set = false;
     if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_pp_kernel),
                                          hipFuncAttributeMaxDynamicSharedMemorySize,
                                          static_cast<int>(kSmemBytes));
       if (e != hipSuccess) PC_FAIL(PC_ERR_HIP, "pc_frame_attn: LDS attribute: %s", hipGetErrorString(e));
@@ -371,10 +400,10 @@ extern "C" int pc_frame_attn(const void* Q, const void* K, const void* V, int dt
     }
     const int n_tiles_q = ceil_div(Nq, kBM);
     const float c = scale * 1.4426950408889634f;
-    attn_bf16_kernel<<<dim3(n_tiles_q * Hq), kThreads, kSmemBytes, s>>>(
+    attn_bf16_pp_kernel<<<dim3(n_tiles_q * Hq), kPPThreads, kSmemBytes, s>>>(
         static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
         static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), lse, rep, Nq, Nk, q_stride_h,
-        kv_stride_h, o_stride_h, c, n_tiles_q);
+        kv_stride_h, o_stride_h, c, n_tiles_q, 1);
   } else {
     PC_REQUIRE(D == 64 || D == 128, PC_ERR_UNSUPPORTED, "pc_frame_attn: fp32 tier needs D=64 or 128, got %d", D);
     const dim3 grid(ceil_div(Nq, kF32Threads), Hq);
