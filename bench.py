@@ -148,7 +148,7 @@ def main() -> int:
         "step_breakdown_ms": {"rope3d": round(rope_ms, 4), "score": round(score_ms, 4),
                               "compact": round(compact_ms, 4), "frame_attn": round(attn_ms, 4)},
         "score_tflops": round(score_flops / (score_ms * 1e-3) / 1e12, 2),
-        "roofline": {"bound": "mfma", "kernel": "attn_bf16_pp_kernel", "achieved": round(attn_tflops, 2),
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
     }

@@ -1,17 +1,17 @@
 // pc_frame_attn: attention of one frame's queries over the keys presented (Eq. 2).
 //
 // bf16 tier (D = 128): flash-style kernel on the gfx950 32x32x16 bf16 MFMA.
-//   * A work-group is 4 waves; each wave owns 64 query rows (two 32-row blocks) of one
-//     query head, so a K/V tile staged in LDS is reused by 256 rows.
 //   * Scores are formed transposed, S^T = K Q^T: in the MFMA result layout a lane then
 //     holds ONE query column and 16 keys per 32-key block.  The running max / sum of a
-//     query are per-lane scalars (one cross-lane exchange per tile), and the probabilities
-//     are already laid out as the B operand of the second product O^T += V^T P^T, so P
-//     never goes through LDS.
-//   * V is transposed on its way into LDS (4 keys x 8 dims per thread, register
-//     shuffle, 8-byte LDS stores) so that the A operand of V^T P^T is one 16-byte LDS read.
-//   * Softmax in fp32 with base-2 exponentials; accumulators are rescaled only when a
-//     row maximum moves.
+//     query are per-lane scalars (one cross-lane exchange per half tile), and the
+//     probabilities are already laid out as the B operand of the second product
+//     O^T += V^T P^T, so P never goes through LDS.
+//   * K and V tiles are fetched straight from global memory into LDS (no register
+//     staging), four tiles deep; V stays row-major in LDS and is transposed by the LDS
+//     transposing read on its way into the MFMA A operand.
+//   * Softmax in fp32 with base-2 exponentials, interleaved instruction by instruction with
+//     the products of the neighbouring half tiles; accumulators are rescaled only when a
+//     row maximum outgrows the reference by 2^8.
 // fp32 tier (D = 64 or 128): one query row per thread, plain FMA; the correctness tier.
 #include <math.h>
 
@@ -21,51 +21,80 @@ namespace pc {
 namespace {
 
 constexpr int kD = 128;
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
-constexpr int kRowsPerWave = 64;
-constexpr int kBM = kWaves * kRowsPerWave;  // 256 query rows per work-group
-constexpr int kBN = 64;                     // keys per tile
-constexpr int kKStride = kD + 8;            // bf16 per K row in LDS (272 B: conflict-free 16-B reads)
-constexpr int kVStride = kBN + 8;           // bf16 per V^T row in LDS (144 B)
-constexpr int kKTile = kBN * kKStride;      // elements
-constexpr int kVTile = kD * kVStride;
-constexpr size_t kSmemBytes = 2 * (kKTile + kVTile) * sizeof(uint16_t);
+constexpr int kPPThreads = 512;      // 8 waves, two per SIMD
+constexpr int kBM = 256;             // query rows per work-group (32 per wave)
+constexpr int kBN = 64;              // keys per tile
+constexpr int kRowBytes = kD * 2;    // a K or V row in LDS: 256 bytes, unpadded, chunk-swizzled
+constexpr int kTileBytes = kBN * kRowBytes;
+constexpr int kStages = 4;           // LDS slots per operand: tile t lives in slot t % kStages
+constexpr size_t kSmemBytes = 2 * kStages * kTileBytes;
+constexpr float kLazyRescale = 8.f;  // base-2 exponent range allowed before re-referencing
+constexpr int kRing = 4;
+
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
 
 __device__ __forceinline__ float wave_half_swap(float v) { return __shfl_xor(v, 32, 64); }
 
-// Position, inside its 16-key step, at which key offset o (0..15) is stored in the V^T
-// tile: the lane group g = bit 2 and the register half a = bit 3 of the MFMA result
-// layout trade places, so a lane's 8 contraction slots are contiguous in LDS.
-__device__ __forceinline__ int vt_slot(int o) {
-  return (o & ~12) | ((o & 4) << 1) | ((o & 8) >> 1);
+// ---- LDS tile layout ---------------------------------------------------------------------------
+// Tiles are filled by direct global->LDS loads: a wave-wide load writes lane i's 16 bytes at
+// base + 16 i, i.e. four whole 256-byte rows back to back, so rows cannot be padded.  Bank
+// conflicts are avoided by choosing WHICH 16-byte chunk of the row each lane fetches:
+//   K: chunk c of row r is stored at chunk position c ^ (r & 15)   (fragment reads: 16 rows, one chunk)
+//   V: chunk c of row r is stored at chunk position c ^ (4 (r & 3)) (transposing reads: 4 rows x 32 bytes)
+__device__ __forceinline__ int k_chunk_pos(int row, int chunk) { return chunk ^ (row & 15); }
+__device__ __forceinline__ int v_chunk_pos(int row, int chunk) { return chunk ^ ((row & 3) << 2); }
+
+// One wave-wide 1-KB direct load: lane i's 16 bytes from `src` land at lds_base + 16 i.
+__device__ __forceinline__ void dma_16B(const void* src, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
+}
+// Wait until at most 4 (kStages - 2) of this wave's direct loads are still in flight: every
+// staging point issues exactly four, so all but the newest kStages - 2 points have landed.
+__device__ __forceinline__ void dma_wait_older() { asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }
+static_assert(kStages == 4, "dma_wait_older encodes 4 * (kStages - 2)");
+
+// Stage tile rows [k0, k0+64) of K or V: each of the 8 waves issues two 1-KB loads.
+template <bool kIsV>
+__device__ __forceinline__ void stage_tile(const uint16_t* __restrict__ base_h, int k0, int Nk, uint32_t lds_tile,
+                                           int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = (wave * 2 + i) * 4 + (lane >> 4);  // 4 rows per load
+    const int pos = lane & 15;                          // chunk position inside the row
+    const int chunk = kIsV ? v_chunk_pos(row, pos) : k_chunk_pos(row, pos);  // both maps are involutions
+    const int key = min(k0 + row, Nk - 1);
+    dma_16B(base_h + static_cast<int64_t>(key) * kD + chunk * 8, lds_tile + (wave * 2 + i) * 1024);
+  }
 }
 
-// ------------------------------------------------------------------------------------------
-// Ping-pong kernel: 8 waves, two per SIMD, 32 query rows each.  The two waves of a SIMD
-// are kept half an iteration apart by the work-group barrier: while one group of four
-// waves is in its MFMA phase (O^T += V^T P^T of the previous tile, then S^T = K Q^T of
-// the current one) the other is in its VALU phase (softmax of its current tile, staging
-// of the next tile into LDS), so the matrix pipe and the vector ALU overlap.
-// Group 0 stages K, group 1 stages V.  LDS buffers alternate per tile.
-// ------------------------------------------------------------------------------------------
-constexpr int kPPThreads = 512;
-constexpr float kLazyRescale = 8.f;  // base-2 exponent range allowed before re-referencing
-
-// One MFMA phase of the ping-pong kernel: the 16 products of O^T += V^T P^T (key step
-// i/4, output block i%4) interleaved one-for-one with the 16 of S^T = K Q^T (contraction
-// step i/2, key block i%2), which gives six independent accumulator chains.  LDS fragment
-// reads run kRing products ahead of their use so the matrix pipe does not wait on LDS.
-__device__ __forceinline__ void pp_mfma_phase(const uint16_t* __restrict__ vt_lane,
-                                              const uint16_t* __restrict__ ks_lane, f32x16 (&o)[4],
-                                              f32x16 (&acc)[2], const bf16x8 (&pf)[4],
-                                              const bf16x8 (&qf)[8]) {
-  constexpr int kRing = 6;
+// One phase of the software pipeline (see the kernel comment): 8 score products and 8
+// value products, alternating, with one element of the probability stage behind each.
+__device__ __forceinline__ void pipeline_phase(
+    const lds_u8* k_half, const int (&k_off)[8], const lds_u8* v_half, const int (&v_off)[4],
+    const bf16x8 (&qf)[8], f32x16& s_nxt, const bf16x8 (&p_mm)[2], f32x16 (&o)[4], const f32x16& s_cur,
+    bf16x8 (&p_cur)[2], float& m_ref, float& l_run, float alpha_cur, float& alpha_nxt, float c,
+    float rescale_threshold) {
+  // fragment k: even -> K rows, contraction step k/2; odd -> V^T (key step (k/2)/4, block (k/2)%4)
   auto frag = [&](int k) -> bf16x8 {
     const int i = k >> 1;
-    if ((k & 1) == 0)
-      return *reinterpret_cast<const bf16x8*>(vt_lane + (i & 3) * 32 * kVStride + (i >> 2) * 16);
-    return *reinterpret_cast<const bf16x8*>(ks_lane + (i & 1) * 32 * kKStride + (i >> 1) * 16);
+    if ((k & 1) == 0) {
+      return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(k_half + k_off[i]);
+    }
+    const int ks = i >> 2, db = i & 3;
+    // keys ks*16 + g*4 + {0..3} and + 8: two transposing reads of 4 keys each
+    const lds_u8* p = v_half + v_off[db] + ks * 16 * kRowBytes;
+    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+        reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(const_cast<lds_u8*>(p)));
+    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+        reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(const_cast<lds_u8*>(p + 8 * kRowBytes)));
+    bf16x8 f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      f[e] = lo[e];
+      f[4 + e] = hi[e];
+    }
+    return f;
   };
   bf16x8 ring[kRing];
 #pragma unroll
@@ -73,41 +102,69 @@ __device__ __forceinline__ void pp_mfma_phase(const uint16_t* __restrict__ vt_la
   f32x16 zero;
 #pragma unroll
   for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+  f32x16 s_acc = zero;
+  float psum = 0.f;
+  float pv[16];
 #pragma unroll
-  for (int k = 0; k < 32; ++k) {
-    const int r = k % kRing, i = k >> 1;
+  for (int k = 0; k < 16; ++k) {
+    const bf16x8 f = ring[k % kRing];
     if ((k & 1) == 0) {
-      o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[r], pf[i >> 2], o[i & 3], 0, 0, 0);
+      s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[k >> 1], k == 0 ? zero : s_acc, 0, 0, 0);
     } else {
-      const int st = i >> 1, kb = i & 1;
-      acc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ring[r], qf[st], st == 0 ? zero : acc[kb], 0, 0, 0);
+      const int ks = (k >> 1) >> 2, db = (k >> 1) & 3;
+      o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, p_mm[ks], o[db], 0, 0, 0);
     }
-    if (k + kRing < 32) ring[r] = frag(k + kRing);
+    if (k + kRing < 16) ring[k % kRing] = frag(k + kRing);
+    pv[k] = __builtin_amdgcn_exp2f(fmaf(s_cur[k], c, -m_ref));
+    psum += pv[k];
+    if (k & 1) {
+      p_cur[k >> 3][(k & 7) - 1] = static_cast<__bf16>(pv[k - 1]);
+      p_cur[k >> 3][k & 7] = static_cast<__bf16>(pv[k]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
-  // pin the issue order: kRing LDS reads up front, then one read behind every product
-  __builtin_amdgcn_sched_group_barrier(0x100, kRing, 0);
+  float mx = s_acc[0];
 #pragma unroll
-  for (int k = 0; k < 32 - kRing; ++k) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-  }
-  __builtin_amdgcn_sched_group_barrier(0x008, kRing, 0);
+  for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s_acc[i]);
+  mx = fmaxf(mx, wave_half_swap(mx)) * c;
+  const float m_new = mx > m_ref + rescale_threshold ? mx : m_ref;
+  alpha_nxt = __builtin_amdgcn_exp2f(m_ref - m_new);
+  l_run = fmaf(l_run, alpha_cur, psum);
+  m_ref = m_new;
+  s_nxt = s_acc;
+  // keep the vector results in this basic block (otherwise they sink below the next branch)
+#pragma unroll
+  for (int half = 0; half < 2; ++half) asm volatile("" : "+v"(p_cur[half]));
+  asm volatile("" : "+v"(l_run), "+v"(alpha_nxt), "+v"(m_ref));
 }
 
-__global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_pp_kernel(
+// ------------------------------------------------------------------------------------------
+// bf16 frame attention.  8 waves (two per SIMD), 32 query rows each, 256 rows per
+// work-group; keys in tiles of 64, processed as half tiles A (keys 0..31) and B (32..63).
+// On this chip matrix and vector instructions overlap only inside one wave's instruction
+// stream, so every wave interleaves, in one basic block per phase,
+//     matrix:  S_nxt^T = K_half Q^T (8 products)  and  O^T += V_half^T P_mm^T (8 products)
+//     vector:  P_cur = exp2(c S_cur - m_ref) and its row sum; then the row maximum of S_nxt
+// where cur is the half tile scored one phase earlier and mm the one before that:
+//     phase 1 of tile j:  S_B(j), O += V_B(j-1) P_B(j-1)  |  P_A(j)
+//     phase 2 of tile j:  S_A(j+1), O += V_A(j) P_A(j)    |  P_B(j)
+// One work-group barrier per tile, after phase 1: behind it K(j+4) and V(j+3) are fetched
+// straight into the LDS slots just released (four slots per operand, 128 KB), three tiles
+// ahead of their first use.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     uint16_t* __restrict__ O, float* __restrict__ lse, int rep, int Nq, int Nk, int64_t q_stride_h,
-    int64_t kv_stride_h, int64_t o_stride_h, float c, int n_tiles_q, int group_shift) {
+    int64_t kv_stride_h, int64_t o_stride_h, float c, int n_tiles_q) {
   extern __shared__ __align__(16) uint8_t smem_raw[];
-  uint16_t* ks_base = reinterpret_cast<uint16_t*>(smem_raw);
-  uint16_t* vt_base = ks_base + 2 * kKTile;
+  lds_u8* smem = (lds_u8*)smem_raw;
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
+  auto k_slot = [&](int t) { return (t & (kStages - 1)) * kTileBytes; };
+  auto v_slot = [&](int t) { return (kStages + (t & (kStages - 1))) * kTileBytes; };
 
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, g = lane >> 5;
-  // the two waves that share a SIMD must land in different groups
-  const int group = group_shift ? (wave >> 2) : (wave & 1);
-  const int wsub = group_shift ? (wave & 3) : (wave >> 1);
   const int L = xcd_contiguous_index(blockIdx.x, gridDim.x);
   const int h = L / n_tiles_q, tile = L % n_tiles_q;
   const int kvh = h / rep;
@@ -130,147 +187,129 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_pp_kernel(
   for (int db = 0; db < 4; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-  f32x16 acc[2];
-  bf16x8 pf[4];
+  f32x16 sA, sB;
+  bf16x8 pA[2], pB[2];
 #pragma unroll
-  for (int k4 = 0; k4 < 4; ++k4)
+  for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) pf[k4][e] = static_cast<__bf16>(0.f);
-  float m_ref = -INFINITY, l_run = 0.f;
-  // V^T buffer 1 is read (against zero probabilities) before its first tile arrives
-  for (int e = threadIdx.x; e < kVTile / 8; e += kPPThreads)
-    reinterpret_cast<u32x4*>(vt_base + kVTile)[e] = u32x4{0u, 0u, 0u, 0u};
+    for (int e = 0; e < 8; ++e) {
+      pA[ks][e] = static_cast<__bf16>(0.f);
+      pB[ks][e] = static_cast<__bf16>(0.f);
+    }
+  float m_ref = -INFINITY, l_run = 0.f, alpha_a = 1.f, alpha_b = 1.f;
 
-  // staging roles: group 0 moves K rows, group 1 moves (and transposes) V
-  const int t256 = wsub * 64 + lane;
-  const int kc = t256 & 15, kr = t256 >> 4;
-  const int kg = lane & 15, dc = wsub * 4 + (lane >> 4);
-  const int vslot = ((kg * 4) & ~15) | vt_slot((kg * 4) & 15);
-  // Two register sets: tile t travels in set t & 1, loaded two tiles ahead of its LDS store.
-  u32x4 pre0[4], pre1[4];
-  auto stage_load = [&](u32x4 (&pre)[4], int t) {
-    const int k0 = t * kBN;
-    if (group == 0) {
+  // per-lane byte offsets inside a half tile
+  int k_off[8];  // K fragment of contraction step s: row l32, chunk 2s+g
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = min(k0 + kr + 16 * i, Nk - 1);
-        pre[i] = *reinterpret_cast<const u32x4*>(Kh + static_cast<int64_t>(key) * kD + kc * 8);
-      }
-    } else {
+  for (int s = 0; s < 8; ++s) k_off[s] = l32 * kRowBytes + k_chunk_pos(l32, 2 * s + g) * 16;
+  int v_off[4];  // V^T fragment of output block db: this lane SUPPLIES row g*4 + r/4, dims db*32 + G*16 + 4(r%4)
+  {
+    const int r = lane & 15, G = (lane >> 4) & 1;
+    const int row = g * 4 + (r >> 2);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int key = min(k0 + kg * 4 + j, Nk - 1);
-        pre[j] = *reinterpret_cast<const u32x4*>(Vh + static_cast<int64_t>(key) * kD + dc * 8);
-      }
+    for (int db = 0; db < 4; ++db) {
+      const int dim = db * 32 + G * 16 + 4 * (r & 3);
+      v_off[db] = row * kRowBytes + v_chunk_pos(row, dim >> 3) * 16 + (dim & 7) * 2;
     }
-  };
-  auto stage_store = [&](const u32x4 (&pre)[4], int t) {
-    const int buf = t & 1;
-    if (group == 0) {
-      uint16_t* ks = ks_base + buf * kKTile;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<u32x4*>(ks + (kr + 16 * i) * kKStride + kc * 8) = pre[i];
-    } else {
-      uint16_t* vt = vt_base + buf * kVTile;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int w = e >> 1;
-        u32x2 out;
-        if (e & 1) {
-          out[0] = (pre[0][w] >> 16) | (pre[1][w] & 0xFFFF0000u);
-          out[1] = (pre[2][w] >> 16) | (pre[3][w] & 0xFFFF0000u);
-        } else {
-          out[0] = (pre[0][w] & 0xFFFFu) | (pre[1][w] << 16);
-          out[1] = (pre[2][w] & 0xFFFFu) | (pre[3][w] << 16);
-        }
-        *reinterpret_cast<u32x2*>(vt + (dc * 8 + e) * kVStride + vslot) = out;
-      }
-    }
-  };
+  }
 
   const int n = (Nk + kBN - 1) / kBN;
-  stage_load(pre0, 0);
-  if (n > 1) stage_load(pre1, 1);
-  if (group == 0) {
-    stage_store(pre0, 0);
-    if (n > 2) stage_load(pre0, 2);
-  }
+  const bool tail = (Nk % kBN) != 0;
+  const int lim_a = Nk - (n - 1) * kBN - g * 4;  // last tile: first invalid key offset, half A
+  const int lim_b = lim_a - 32;
+
+  // the V slot of "tile -1" is read once against zero probabilities: clear it
+  for (int e = threadIdx.x; e < kTileBytes / 16; e += kPPThreads)
+    reinterpret_cast<__attribute__((address_space(3))) u32x4*>(smem + v_slot(-1))[e] = u32x4{0u, 0u, 0u, 0u};
+  // Prologue, in order of need: K(0), V(0), K(1), then K(2), V(1), K(3), V(2).  Tiles past the
+  // end of the cache are fetched too (clamped rows, never read) so that every staging point
+  // issues the same number of loads and the in-flight count can be waited on.
+  stage_tile<false>(Kh, 0, Nk, lds0 + k_slot(0), wave, lane);
+  stage_tile<true>(Vh, 0, Nk, lds0 + v_slot(0), wave, lane);
+  stage_tile<false>(Kh, kBN, Nk, lds0 + k_slot(1), wave, lane);
+  stage_tile<false>(Kh, 2 * kBN, Nk, lds0 + k_slot(2), wave, lane);
+  stage_tile<true>(Vh, kBN, Nk, lds0 + v_slot(1), wave, lane);
+  stage_tile<false>(Kh, 3 * kBN, Nk, lds0 + k_slot(3), wave, lane);
+  stage_tile<true>(Vh, 2 * kBN, Nk, lds0 + v_slot(2), wave, lane);
+  dma_wait_older();
   __syncthreads();
 
-  for (int p = 0; p < 2 * n + 2; ++p) {
-    const int j = (p - group) >> 1;  // tile this group works on (-1 / n: nothing to compute)
-    if (((p + group) & 1) == 0) {
-      // ---------------- MFMA phase: PV of tile j-1, then S of tile j ----------------
-      if (active) {
-        __builtin_amdgcn_s_setprio(1);
-        const uint16_t* vt_lane = vt_base + ((j - 1) & 1) * kVTile + l32 * kVStride + g * 8;
-        const uint16_t* ks_lane = ks_base + (j & 1) * kKTile + l32 * kKStride + g * 8;
-        // Always both products: at j = 0 the P fragments are zero and the V^T buffer was
-        // zero-filled, at j = n the scores computed from a stale K buffer are never used.
-        pp_mfma_phase(vt_lane, ks_lane, o, acc, pf, qf);
-        __builtin_amdgcn_s_setprio(0);
-      }
-    } else {
-      // ---------------- VALU phase: softmax of tile j, stage tile j+1 ----------------
-      if (active && j >= 0 && j < n) {
-        const int k0 = j * kBN;
-        if (k0 + kBN > Nk) {
-          const int lim = Nk - k0 - g * 4;  // first invalid key offset, seen from this lane
+  auto mask_tail = [&](f32x16& sc, int lim) {
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
+    for (int i = 0; i < 16; ++i)
+      if ((i >> 2) * 8 + (i & 3) >= lim) sc[i] = -INFINITY;
+  };
+  auto rescale = [&](float alpha) {
+    if (__any(alpha != 1.f)) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-              if (kb * 32 + (i >> 2) * 8 + (i & 3) >= lim) acc[kb][i] = -INFINITY;
-        }
-        float mx = acc[0][0];
+      for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[kb][i]);
-        mx = fmaxf(mx, wave_half_swap(mx)) * c;
-        if (__any(mx > m_ref + kLazyRescale)) {
-          const float m_new = mx > m_ref + kLazyRescale ? mx : m_ref;
-          const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
-          l_run *= alpha;
-#pragma unroll
-          for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-          m_ref = m_new;
-        }
-        float psum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          float pv[16];
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            pv[i] = __builtin_amdgcn_exp2f(fmaf(acc[kb][i], c, -m_ref));
-            psum += pv[i];
-          }
-#pragma unroll
-          for (int half = 0; half < 2; ++half) {
-            bf16x8 f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) f[e] = static_cast<__bf16>(pv[half * 8 + e]);
-            pf[kb * 2 + half] = f;
-          }
-        }
-        l_run += psum;
-      }
-      const int t = j + 1;
-      if (t & 1) {
-        if (t < n) stage_store(pre1, t);
-        if (t + 2 < n) stage_load(pre1, t + 2);
-      } else {
-        if (t < n) stage_store(pre0, t);
-        if (t + 2 < n) stage_load(pre0, t + 2);
-      }
+        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
     }
-    __syncthreads();
+  };
+  if (active) {  // S_A of tile 0 and the first reference maximum
+    f32x16 zero;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const bf16x8 kf = *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(smem + k_slot(0) + k_off[s]);
+      sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? zero : sA, 0, 0, 0);
+    }
+    float mx = sA[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sA[i]);
+    m_ref = fmaxf(mx, wave_half_swap(mx)) * c;
+    if (tail && n == 1) mask_tail(sA, lim_a);
   }
 
+  for (int j = 0; j < n; ++j) {
+    const bool last = j + 1 == n;
+    // ---- phase 1: S_B(j), O += V_B(j-1) P_B(j-1)  |  P_A(j), max S_B(j) ----
+    if (active) {
+      pipeline_phase(smem + k_slot(j) + 32 * kRowBytes, k_off, smem + v_slot(j - 1) + 32 * kRowBytes, v_off, qf, sB, pB,
+                     o, sA, pA, m_ref, l_run, alpha_a, alpha_b, c, kLazyRescale);
+      rescale(alpha_a);
+      if (last && tail) mask_tail(sB, lim_b);
+    }
+    // One barrier per tile: every wave is past K(j) and V(j-1), and K(j+1), V(j) (fetched
+    // kStages - 1 tiles ago) have landed: each wave waited for its own share.
+    dma_wait_older();
+    __syncthreads();
+    stage_tile<false>(Kh, (j + kStages) * kBN, Nk, lds0 + k_slot(j), wave, lane);
+    stage_tile<true>(Vh, (j + kStages - 1) * kBN, Nk, lds0 + v_slot(j - 1), wave, lane);
+    // ---- phase 2: S_A(j+1), O += V_A(j) P_A(j)  |  P_B(j), max S_A(j+1) ----
+    // (after the last tile S_A is formed from a clamped tile: an infinite threshold keeps
+    // its values from moving the reference maximum)
+    if (active) {
+      pipeline_phase(smem + k_slot(j + 1), k_off, smem + v_slot(j), v_off, qf, sA, pA, o, sB, pB, m_ref, l_run,
+                     alpha_b, alpha_a, c, last ? INFINITY : kLazyRescale);
+      rescale(alpha_b);
+      if (j + 2 == n && tail) mask_tail(sA, lim_a);
+    }
+  }
   if (!active) return;
+  // ---- drain: O += V_B(n-1) P_B(n-1) ----
+  {
+    const lds_u8* v_half = smem + v_slot(n - 1) + 32 * kRowBytes;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const lds_u8* p = v_half + v_off[db] + ks * 16 * kRowBytes;
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(const_cast<lds_u8*>(p)));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            reinterpret_cast<__attribute__((address_space(3))) bf16x4*>(const_cast<lds_u8*>(p + 8 * kRowBytes)));
+        bf16x8 vf;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          vf[e] = lo[e];
+          vf[4 + e] = hi[e];
+        }
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pB[ks], o[db], 0, 0, 0);
+      }
+  }
   const float l_tot = l_run + wave_half_swap(l_run);
   const float inv = 1.f / l_tot;
   const int row = row0 + l32;
@@ -392,7 +431,7 @@ extern "C" int pc_frame_attn(const void* Q, const void* K, const void* V, int dt
                PC_ERR_SHAPE, "pc_frame_attn: bf16 tensors and head strides must be 16-byte aligned");
     static bool attr_set = false;
     if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_pp_kernel),
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel),
                                          hipFuncAttributeMaxDynamicSharedMemorySize,
                                          static_cast<int>(kSmemBytes));
       if (e != hipSuccess) PC_FAIL(PC_ERR_HIP, "pc_frame_attn: LDS attribute: %s", hipGetErrorString(e));
@@ -400,10 +439,10 @@ extern "C" int pc_frame_attn(const void* Q, const void* K, const void* V, int dt
     }
     const int n_tiles_q = ceil_div(Nq, kBM);
     const float c = scale * 1.4426950408889634f;
-    attn_bf16_pp_kernel<<<dim3(n_tiles_q * Hq), kPPThreads, kSmemBytes, s>>>(
+    attn_bf16_kernel<<<dim3(n_tiles_q * Hq), kPPThreads, kSmemBytes, s>>>(
         static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
         static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), lse, rep, Nq, Nk, q_stride_h,
-        kv_stride_h, o_stride_h, c, n_tiles_q, 1);
+        kv_stride_h, o_stride_h, c, n_tiles_q);
   } else {
     PC_REQUIRE(D == 64 || D == 128, PC_ERR_UNSUPPORTED, "pc_frame_attn: fp32 tier needs D=64 or 128, got %d", D);
     const dim3 grid(ceil_div(Nq, kF32Threads), Hq);
