@@ -14,7 +14,7 @@ __all__ = [
     "PC_BUDGET_POW", "PC_BUDGET_NORM", "PC_BUDGET_HALF", "PC_BUDGET_SLIDE", "PC_MAX_SEGMENTS",
     "PackCacheError", "lib", "lib_path", "pc_version", "pc_strerror", "pc_budget", "pc_rope3d",
     "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact",
-    "pc_compact_workspace_bytes", "pc_frame_attn", "pc_frame_attn_workspace_bytes",
+    "pc_compact_workspace_bytes", "pc_compact_prepared", "pc_frame_attn", "pc_frame_attn_workspace_bytes",
     "segment_budgets",
 ]
 
@@ -209,6 +209,25 @@ def pc_compact(K, V, pos, score, segments, budgets, share_heads: bool = False, o
                             _ptr(idx), 0 if idx is None else idx.stride(0), seg_out, C.byref(nk),
                             ws.data_ptr(), ws.numel(), _stream()))
     return [(s.start, s.len, s.kind, s.frame) for s in seg_out[:n]], nk.value
+
+
+def pc_compact_prepared(K, V, pos, score, segments, budgets, ws, share_heads: bool = False, out=None, idx=None):
+    """Marshal the arguments of pc_compact once; returns a callable that only makes the C
+    call (for launch loops where Python-side marshalling would dominate)."""
+    Hkv, _, D = K.shape
+    n = len(segments)
+    seg_in = _seg_array(segments)
+    b = (C.c_int32 * max(n, 1))(*[int(v) for v in budgets])
+    Ko, Vo, po = (K, V, pos) if out is None else out
+    fn = lib().pc_compact
+    args = (K.data_ptr(), V.data_ptr(), pos.data_ptr(), _dtype_code(K), Hkv, D, K.stride(0), pos.stride(0),
+            score.data_ptr(), score.stride(0), seg_in, n, b, int(share_heads), Ko.data_ptr(), Vo.data_ptr(),
+            po.data_ptr(), Ko.stride(0), po.stride(0), _ptr(idx), 0 if idx is None else idx.stride(0), None, None,
+            ws.data_ptr(), ws.numel(), _stream())
+
+    def call():
+        _check(fn(*args))
+    return call
 
 
 def pc_frame_attn_workspace_bytes(Hq: int, Nq: int, Nk: int, D: int) -> int:

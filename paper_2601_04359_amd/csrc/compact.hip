@@ -22,7 +22,6 @@ namespace {
 
 constexpr int kGatherRows = 32;   // packed rows per gather work-group
 constexpr int kGatherThreads = 256;
-constexpr int kMaxItems = 8;      // 16-byte items per thread: rows*chunks_per_row*2/threads
 constexpr int kSpinLimit = 1 << 22;
 
 struct SegTable {
@@ -122,65 +121,195 @@ __global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ sc
   select_wave<kItems>(score + h * score_stride_h + start, len, keep, out, start);
 }
 
-// ---- gather ----------------------------------------------------------------------------------
-struct GatherSync {
-  int32_t ticket;
-  int32_t abort;
-  int32_t pad[62];
-};
-
-__global__ void gather_init(GatherSync* sync, int32_t* flags, int n_flags) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i == 0) {
-    sync->ticket = 0;
-    sync->abort = 0;
+// Four waves per segment: wave w owns the contiguous slice [w * 64 kItems, (w+1) * 64 kItems)
+// of the segment, kItems keys per lane in registers.  The k-th largest key is found eight
+// bits at a time: keys that still match the prefix vote into a 256-bin LDS histogram, the
+// 256 threads take a suffix sum over the bins (wave scan + one exchange) and the bin that
+// contains the k-th key extends the prefix.  The ordered output needs one more exchange
+// (keys above the threshold and keys equal to it, per wave).
+// Blocks also clear the in-place gather's ticket counters and flags (n_clear words).
+template <int kItems>
+__global__ __launch_bounds__(256) void select_block_kernel(const float* __restrict__ score,
+                                                           int64_t score_stride_h,
+                                                           int32_t* __restrict__ idx, int64_t idx_stride_h,
+                                                           SegTable tab, int32_t* __restrict__ clear,
+                                                           int n_clear) {
+  __shared__ int s_hist[256];
+  __shared__ int s_wave_sum[4];
+  __shared__ int s_pick[2];  // chosen digit, keys above it
+  __shared__ int s_gt[4], s_eq[4];
+  const int s = blockIdx.x, h = blockIdx.y;
+  {
+    const int nb = gridDim.x * gridDim.y, b = h * gridDim.x + s;
+    for (int i = b * 256 + threadIdx.x; i < n_clear; i += nb * 256) clear[i] = 0;
   }
-  if (i < n_flags) flags[i] = 0;
+  const int start = tab.start[s], len = tab.len[s], k = tab.keep[s];
+  int32_t* out = idx + h * idx_stride_h + tab.dst[s];
+  if (k <= 0) return;  // block-uniform
+  if (!tab.prune[s]) {
+    for (int e = threadIdx.x; e < len; e += 256) out[e] = start + e;
+    return;
+  }
+  const float* sc = score + h * score_stride_h + start;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const int base = wave * 64 * kItems;
+  uint32_t key[kItems];
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    const int e = base + i * 64 + lane;
+    key[i] = e < len ? order_key(sc[e]) : 0u;  // 0 is below every real key
+  }
+  // Bits shared by every key of the segment (sign, most of the exponent) are settled at
+  // once: only the bits from the highest differing one down go through the histogram,
+  // which also keeps the votes from piling onto a single bin.
+  uint32_t k_and = 0xFFFFFFFFu, k_or = 0u;
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    if (base + i * 64 + lane < len) {
+      k_and &= key[i];
+      k_or |= key[i];
+    }
+  }
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) {
+    k_and &= __shfl_xor(k_and, d, 64);
+    k_or |= __shfl_xor(k_or, d, 64);
+  }
+  if (lane == 0) {
+    s_gt[wave] = static_cast<int>(k_and);
+    s_eq[wave] = static_cast<int>(k_or);
+  }
+  __syncthreads();
+  k_and = static_cast<uint32_t>(s_gt[0] & s_gt[1] & s_gt[2] & s_gt[3]);
+  k_or = static_cast<uint32_t>(s_eq[0] | s_eq[1] | s_eq[2] | s_eq[3]);
+  __syncthreads();
+  const uint32_t differ = k_and ^ k_or;
+  int hi = differ ? 32 - __clz(differ) : 0;  // number of undecided low bits
+  uint32_t prefix = hi >= 32 ? 0u : (k_or >> hi) << hi;
+  int remaining = k;
+  while (hi > 0) {
+    const int width = min(8, hi), shift = hi - width;
+    s_hist[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t hi_mask = hi >= 32 ? 0u : 0xFFFFFFFFu << hi;
+    const uint32_t digit_mask = (1u << width) - 1u;
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) {
+      const int e = base + i * 64 + lane;
+      if (e < len && (key[i] & hi_mask) == (prefix & hi_mask)) atomicAdd(&s_hist[(key[i] >> shift) & digit_mask], 1);
+    }
+    __syncthreads();
+    // suffix sums: above = number of matching keys with a digit larger than this thread's
+    const int mine = s_hist[threadIdx.x];
+    int incl = mine;  // inclusive suffix sum inside the wave (towards higher lanes)
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int v = __shfl_down(incl, d, 64);
+      if (lane + d < 64) incl += v;
+    }
+    if (lane == 0) s_wave_sum[wave] = incl;
+    __syncthreads();
+    int above = incl - mine;
+    for (int w = wave + 1; w < 4; ++w) above += s_wave_sum[w];
+    if (above < remaining && remaining <= above + mine) {  // exactly one thread
+      s_pick[0] = threadIdx.x;
+      s_pick[1] = above;
+    }
+    __syncthreads();
+    prefix |= static_cast<uint32_t>(s_pick[0]) << shift;
+    remaining -= s_pick[1];
+    hi = shift;
+  }
+  int gt = 0, eq = 0;
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    gt += popc64(__ballot(key[i] > prefix));
+    eq += popc64(__ballot(key[i] == prefix));
+  }
+  if (lane == 0) {
+    s_gt[wave] = gt;
+    s_eq[wave] = eq;
+  }
+  __syncthreads();
+  int out_run = 0, eq_run = 0;  // kept keys / threshold keys in the waves before this one
+  for (int w = 0; w < wave; ++w) {
+    const int take = min(s_eq[w], max(remaining - eq_run, 0));
+    out_run += s_gt[w] + take;
+    eq_run += s_eq[w];
+  }
+#pragma unroll
+  for (int i = 0; i < kItems; ++i) {
+    const int e = base + i * 64 + lane;
+    const uint32_t kv = key[i];
+    const bool is_eq = kv == prefix;  // padding keys are 0 < prefix
+    const uint64_t beq = __ballot(is_eq);
+    const bool kept = kv > prefix || (is_eq && eq_run + popc64(beq & lt_mask) < remaining);
+    const uint64_t bk = __ballot(kept);
+    const int at = out_run + popc64(bk & lt_mask);
+    if (kept && at < k) out[at] = start + e;
+    out_run += popc64(bk);
+    eq_run += popc64(beq);
+  }
 }
 
-template <bool kInPlace>
+// ---- gather ----------------------------------------------------------------------------------
+constexpr int kMaxTicketHeads = 64;
+struct GatherSync {  // one ticket counter per KV head, each on its own 128-byte line
+  int32_t abort;
+  int32_t pad[31];
+  int32_t ticket[kMaxTicketHeads][32];
+};
+
+__global__ void clear_words(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+template <int cpr /* 16-byte chunks per row */, int kRows /* packed rows per work-group */, bool kInPlace>
 __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     const u32x4* __restrict__ K, const u32x4* __restrict__ V, const int32_t* __restrict__ pos,
     u32x4* __restrict__ Ko, u32x4* __restrict__ Vo, int32_t* __restrict__ pos_o,
     const int32_t* __restrict__ idx, int64_t idx_stride_h, int share_heads, int Hkv, int Nk_in, int Nk_out,
-    int cpr /* 16-byte chunks per row */, int64_t in_stride_c, int64_t out_stride_c,
+    int64_t in_stride_c, int64_t out_stride_c,
     int64_t pos_stride_h, int64_t pos_out_stride_h, GatherSync* sync, int32_t* flags,
     int chunks_per_head, SegTable tab) {
   __shared__ int s_ticket;
-  int work = blockIdx.x;
-  if constexpr (kInPlace) {
-    if (threadIdx.x == 0) s_ticket = atomicAdd(&sync->ticket, 1);
+  const int h = blockIdx.x % Hkv;
+  int cc = blockIdx.x / Hkv;
+  if constexpr (kInPlace) {  // chunks of a head are taken in ticket order, not in launch order
+    if (threadIdx.x == 0) s_ticket = atomicAdd(&sync->ticket[h][0], 1);
     __syncthreads();
-    work = s_ticket;
+    cc = s_ticket;
   }
-  const int h = work % Hkv, cc = work / Hkv;
   const int hs = share_heads ? 0 : h;
-  const int r0 = cc * kGatherRows;
-  const int r1 = min(r0 + kGatherRows, Nk_out);
-  const int n_items = (r1 - r0) * cpr * 2;
+  const int r0 = cc * kRows;
+  const int r1 = min(r0 + kRows, Nk_out);
   const int32_t* idx_h = idx + hs * idx_stride_h;
 
-  // ---- load ----
-  u32x4 val[kMaxItems];
-  int64_t dst_off[kMaxItems];
+  // ---- load: a thread moves one 16-byte chunk of a K row and the same chunk of its V row ----
+  constexpr int kRowsPerPass = kGatherThreads / cpr;
+  constexpr int kPasses = kRows / kRowsPerPass;
+  const int ch = threadIdx.x % cpr, rp = threadIdx.x / cpr;
+  u32x4 kval[kPasses], vval[kPasses];
+  int64_t dst_off[kPasses];
 #pragma unroll
-  for (int it = 0; it < kMaxItems; ++it) {
-    const int item = it * kGatherThreads + threadIdx.x;
+  for (int it = 0; it < kPasses; ++it) {
+    const int row = r0 + it * kRowsPerPass + rp;
     dst_off[it] = -1;
-    if (item < n_items) {
-      const int which = item >= (r1 - r0) * cpr;  // 0: K, 1: V
-      const int e = which ? item - (r1 - r0) * cpr : item;
-      const int row = r0 + e / cpr, ch = e % cpr;
+    if (row < r1) {
       const int src = min(max(idx_h[row], 0), Nk_in - 1);  // a valid table never needs the clamp
       if (!kInPlace || src != row) {
-        const u32x4* base = which ? V : K;
-        val[it] = base[h * in_stride_c + static_cast<int64_t>(src) * cpr + ch];
-        dst_off[it] = (static_cast<int64_t>(which) << 62) | (h * out_stride_c + static_cast<int64_t>(row) * cpr + ch);
+        const int64_t so = h * in_stride_c + static_cast<int64_t>(src) * cpr + ch;
+        kval[it] = K[so];
+        vval[it] = V[so];
+        dst_off[it] = h * out_stride_c + static_cast<int64_t>(row) * cpr + ch;
       }
     }
   }
   int32_t pval = 0;
   int64_t pdst = -1;
+  static_assert(kRows * 3 <= kGatherThreads, "one thread per position component");
   if ((share_heads ? h == 0 : true) && threadIdx.x < (r1 - r0) * 3) {
     const int row = r0 + threadIdx.x / 3, comp = threadIdx.x % 3;
     const int src = min(max(idx_h[row], 0), Nk_in - 1);
@@ -198,7 +327,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     // loads), the work-group barrier collects all threads, and relaxed device-scope
     // accesses carry the flag.
 #pragma unroll
-    for (int it = 0; it < kMaxItems; ++it) asm volatile("" : "+v"(val[it]));
+    for (int it = 0; it < kPasses; ++it) asm volatile("" : "+v"(kval[it]), "+v"(vval[it]));
     asm volatile("" : "+v"(pval));
     __syncthreads();
     int32_t* flags_h = flags + h * chunks_per_head;
@@ -206,9 +335,20 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
       __hip_atomic_store(&flags_h[cc], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // Source row of the i-th kept row of a segment: start + i <= src <= start + (len - keep) + i.
     int row_lo = INT_MAX, row_hi = -1;
-    for (int s = 0; s < tab.n; ++s) {
-      const int a = tab.start[s], b = a + tab.len[s];
-      if (b <= r0 || a >= r1 || tab.keep[s] <= 0) continue;
+    int first = 0;  // first segment that ends behind r0 (segments are in row order): binary search
+    for (int lo = 0, hi = tab.n; lo < hi;) {
+      const int mid = (lo + hi) >> 1;
+      if (tab.start[mid] + tab.len[mid] <= r0) {
+        lo = mid + 1;
+        first = lo;
+      } else {
+        hi = mid;
+        first = lo;
+      }
+    }
+    for (int s = first; s < tab.n && tab.start[s] < r1; ++s) {
+      if (tab.keep[s] <= 0) continue;
+      const int a = tab.start[s];
       const int slack = tab.len[s] - tab.keep[s];
       const int i_lo = max(0, r0 - a - slack), i_hi = min(tab.keep[s] - 1, r1 - 1 - a);
       if (i_lo <= i_hi) {
@@ -217,7 +357,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
       }
     }
     if (row_hi >= 0) {
-      const int c_lo = row_lo / kGatherRows, c_hi = min(row_hi / kGatherRows, cc - 1);
+      const int c_lo = row_lo / kRows, c_hi = min(row_hi / kRows, cc - 1);
       for (int c = c_lo + threadIdx.x; c <= c_hi; c += kGatherThreads) {
         int spins = 0;
         while (__hip_atomic_load(&flags_h[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) {
@@ -235,10 +375,10 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
 
   // ---- store ----
 #pragma unroll
-  for (int it = 0; it < kMaxItems; ++it) {
+  for (int it = 0; it < kPasses; ++it) {
     if (dst_off[it] >= 0) {
-      u32x4* base = (dst_off[it] >> 62) ? Vo : Ko;
-      base[dst_off[it] & ((1ll << 62) - 1)] = val[it];
+      Ko[dst_off[it]] = kval[it];
+      Vo[dst_off[it]] = vval[it];
     }
   }
   if (pdst >= 0) pos_o[pdst] = pval;
@@ -297,9 +437,8 @@ extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, in
 
   const int elt = dtype == PC_BF16 ? 2 : 4;
   const int row_bytes = D * elt;
-  PC_REQUIRE(row_bytes % 16 == 0 && row_bytes / 16 <= 4 * kMaxItems, PC_ERR_UNSUPPORTED,
-             "pc_compact: row of %d bytes (must be a multiple of 16, at most %d)", row_bytes,
-             64 * kMaxItems);
+  PC_REQUIRE(row_bytes == 256 || row_bytes == 512, PC_ERR_UNSUPPORTED,
+             "pc_compact: rows of %d bytes (supported: 256 and 512)", row_bytes);
   PC_REQUIRE(K && V && pos && score && K_out && V_out && pos_out, PC_ERR_NULL,
              "pc_compact: K, V, pos, score or an output is NULL");
   const bool in_place = K_out == K;
@@ -348,34 +487,48 @@ extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, in
   int32_t* flags = reinterpret_cast<int32_t*>(wsb + lay.flags_off);
 
   const dim3 sgrid(n_seg, hsel);
+  // the select kernel also clears the in-place gather's counters and flags (contiguous in ws)
+  int32_t* clear = in_place ? reinterpret_cast<int32_t*>(sync) : nullptr;
+  const int n_clear = in_place ? static_cast<int>((lay.total - lay.sync_off) / sizeof(int32_t)) : 0;
   if (max_prune_len <= 256)
-    select_kernel<4><<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab);
+    select_block_kernel<1><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear);
   else if (max_prune_len <= 1024)
-    select_kernel<16><<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab);
+    select_block_kernel<4><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear);
   else if (max_prune_len <= PC_MAX_SELECT_LEN)
-    select_kernel<64><<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab);
+    select_block_kernel<16><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear);
   else
+  {
     select_kernel<0><<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab);
+    if (in_place) {
+      PC_CHECK_LAUNCH("pc_compact select");
+      clear_words<<<ceil_div(n_clear, 256), 256, 0, st>>>(clear, n_clear);
+    }
+  }
   PC_CHECK_LAUNCH("pc_compact select");
 
   const int cpr = row_bytes / 16;
-  const int chunks_per_head = ceil_div(nk_out, kGatherRows);
+  constexpr int kRowsInPlace = 64;
+  const int rows_per_group = in_place ? kRowsInPlace : kGatherRows;
+  const int chunks_per_head = ceil_div(nk_out, rows_per_group);
   const int64_t in_stride_c = kv_stride_h * elt / 16, out_stride_c = kv_out_stride_h * elt / 16;
   const dim3 ggrid(chunks_per_head * Hkv);
   if (in_place) {
-    const int n_flags = Hkv * lay.chunks_per_head;
-    gather_init<<<ceil_div(n_flags, 256), 256, 0, st>>>(sync, flags, n_flags);
-    PC_CHECK_LAUNCH("pc_compact init");
-    gather_kernel<true><<<ggrid, kGatherThreads, 0, st>>>(
-        static_cast<const u32x4*>(K), static_cast<const u32x4*>(V), pos, static_cast<u32x4*>(K_out),
-        static_cast<u32x4*>(V_out), pos_out, idx, idx_stride, share_heads, Hkv, nk_in, nk_out, cpr, in_stride_c,
-        out_stride_c, pos_stride_h, pos_out_stride_h, sync, flags, lay.chunks_per_head, tab);
-  } else {
-    gather_kernel<false><<<ggrid, kGatherThreads, 0, st>>>(
-        static_cast<const u32x4*>(K), static_cast<const u32x4*>(V), pos, static_cast<u32x4*>(K_out),
-        static_cast<u32x4*>(V_out), pos_out, idx, idx_stride, share_heads, Hkv, nk_in, nk_out, cpr, in_stride_c,
-        out_stride_c, pos_stride_h, pos_out_stride_h, sync, flags, lay.chunks_per_head, tab);
+    PC_REQUIRE(Hkv <= kMaxTicketHeads, PC_ERR_UNSUPPORTED, "pc_compact: in place supports at most %d KV heads",
+               kMaxTicketHeads);
   }
+#define PC_LAUNCH_GATHER(CPR, ROWS, INPLACE)                                                             \
+  gather_kernel<CPR, ROWS, INPLACE><<<ggrid, kGatherThreads, 0, st>>>(                                   \
+      static_cast<const u32x4*>(K), static_cast<const u32x4*>(V), pos, static_cast<u32x4*>(K_out),       \
+      static_cast<u32x4*>(V_out), pos_out, idx, idx_stride, share_heads, Hkv, nk_in, nk_out, in_stride_c, \
+      out_stride_c, pos_stride_h, pos_out_stride_h, sync, flags, lay.chunks_per_head, tab)
+  if (cpr == 16) {
+    if (in_place) PC_LAUNCH_GATHER(16, kRowsInPlace, true); else PC_LAUNCH_GATHER(16, kGatherRows, false);
+  } else if (cpr == 32) {
+    if (in_place) PC_LAUNCH_GATHER(32, kRowsInPlace, true); else PC_LAUNCH_GATHER(32, kGatherRows, false);
+  } else {
+    PC_FAIL(PC_ERR_UNSUPPORTED, "pc_compact: rows of %d bytes (supported: 256 and 512)", row_bytes);
+  }
+#undef PC_LAUNCH_GATHER
   PC_CHECK_LAUNCH("pc_compact gather");
   return PC_OK;
 }
