@@ -15,7 +15,7 @@
 // fp32 tier (D = 64 or 128): one query row per thread, plain FMA; the correctness tier.
 #include <math.h>
 
-#include "common.h"
+#include "lds_dma.h"
 
 namespace pc {
 namespace {
@@ -31,24 +31,11 @@ constexpr size_t kSmemBytes = 2 * kStages * kTileBytes;
 constexpr float kLazyRescale = 8.f;  // base-2 exponent range allowed before re-referencing
 constexpr int kRing = 4;
 
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((address_space(3))) uint8_t lds_u8;
-
-__device__ __forceinline__ float wave_half_swap(float v) { return __shfl_xor(v, 32, 64); }
-
 // ---- LDS tile layout ---------------------------------------------------------------------------
-// Tiles are filled by direct global->LDS loads: a wave-wide load writes lane i's 16 bytes at
-// base + 16 i, i.e. four whole 256-byte rows back to back, so rows cannot be padded.  Bank
-// conflicts are avoided by choosing WHICH 16-byte chunk of the row each lane fetches:
-//   K: chunk c of row r is stored at chunk position c ^ (r & 15)   (fragment reads: 16 rows, one chunk)
-//   V: chunk c of row r is stored at chunk position c ^ (4 (r & 3)) (transposing reads: 4 rows x 32 bytes)
-__device__ __forceinline__ int k_chunk_pos(int row, int chunk) { return chunk ^ (row & 15); }
+// K tiles use the fragment-read swizzle of lds_dma.h.  V is read with transposing loads
+// (4 rows x 32 bytes per quarter wave): chunk c of row r is stored at position c ^ (4 (r & 3)).
 __device__ __forceinline__ int v_chunk_pos(int row, int chunk) { return chunk ^ ((row & 3) << 2); }
 
-// One wave-wide 1-KB direct load: lane i's 16 bytes from `src` land at lds_base + 16 i.
-__device__ __forceinline__ void dma_16B(const void* src, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
-}
 // Wait until at most 4 (kStages - 2) of this wave's direct loads are still in flight: every
 // staging point issues exactly four, so all but the newest kStages - 2 points have landed.
 __device__ __forceinline__ void dma_wait_older() { asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); }

@@ -1,0 +1,33 @@
+// Direct global->LDS tile loads and the swizzled 256-byte-row tile layout shared by the
+// bf16 MFMA kernels (gfx950 only).
+#pragma once
+
+#include "common.h"
+
+namespace pc {
+
+typedef __attribute__((address_space(3))) uint8_t lds_u8;
+
+__device__ __forceinline__ float wave_half_swap(float v) { return __shfl_xor(v, 32, 64); }
+
+// Tiles are filled by direct global->LDS loads: a wave-wide load writes lane i's 16 bytes at
+// base + 16 i, i.e. four whole 256-byte rows back to back, so rows cannot be padded.  Bank
+// conflicts are avoided by choosing WHICH 16-byte chunk of the row each lane fetches: for an
+// operand read as MFMA fragments (16 rows, one chunk each per quarter wave) chunk c of row r
+// is stored at chunk position c ^ (r & 15).  The map is an involution.
+__device__ __forceinline__ int k_chunk_pos(int row, int chunk) { return chunk ^ (row & 15); }
+
+// One wave-wide 1-KB direct load: lane i's 16 bytes from `src` land at lds_base + 16 i.
+__device__ __forceinline__ void dma_16B(const void* src, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
+}
+// One wave-wide 256-byte direct load: lane i's 4 bytes from `src` land at lds_base + 4 i.
+__device__ __forceinline__ void dma_4B(const void* src, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(src) : "memory");
+}
+
+__device__ __forceinline__ bf16x8 lds_frag(const lds_u8* p) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(p);
+}
+
+}  // namespace pc

@@ -5,257 +5,385 @@
 // result is bit-reproducible:
 //   1. row pass:    log-sum-exp of every scoring query over all keys (keys split over
 //                   work-groups, partial (max, sum) pairs merged in a fixed order);
-//   2. column pass: key-stationary.  A work-group owns 256 keys (staged once in LDS),
-//                   streams all scoring queries of the KV group past them, forms
-//                   p = exp2(c*s - lse2) with the FINAL normaliser, un-rounded, in fp32,
-//                   and sums p down the query axis.
+//   2. column pass: p = exp2(c*s - lse2) with the FINAL normaliser, un-rounded, in fp32,
+//                   summed down the query axis (queries split over work-groups, partial
+//                   sums added in a fixed order).
 // A caller that already has the log-sum-exp skips pass 1.
+//
+// Both passes have the same shape.  One operand is stationary: every wave keeps 64 of its
+// rows as MFMA fragments in registers for the whole kernel (queries in pass 1, keys in
+// pass 2).  The other operand streams through a four-slot LDS ring in tiles of 64 rows,
+// fetched by direct global->LDS loads three tiles ahead, one work-group barrier per tile.
+// Each element of the product costs one exponential, so both passes are bound by the vector
+// pipe, not the matrix pipe; matrix and vector instructions overlap only inside one wave's
+// instruction stream, so every wave interleaves the 16 products of the next half tile with
+// the exponentials of the one before.
 #include <math.h>
 
 #include <algorithm>
 
-#include "common.h"
+#include "lds_dma.h"
 
 namespace pc {
 namespace {
 
 constexpr int kD = 128;
-constexpr int kThreads = 256;
-constexpr int kKStride = kD + 8;  // bf16 per key row in LDS
-constexpr int kMaxSplits = 32;
+constexpr int kThreads = 512;        // 8 waves, two per SIMD
+constexpr int kWaveRows = 64;        // stationary rows per wave (two 32-row MFMA blocks)
+constexpr int kBlockRows = 8 * kWaveRows;
+constexpr int kTileRows = 64;        // streamed rows per LDS slot
+constexpr int kRowBytes = kD * 2;
+constexpr int kTileBytes = kTileRows * kRowBytes;
+constexpr int kStages = 4;
+constexpr int kLseSlotBytes = kTileRows * 4;
+constexpr size_t kRowSmem = kStages * kTileBytes;
+constexpr size_t kColSmem = kStages * (kTileBytes + kLseSlotBytes);
+constexpr int kMaxSplits = 32;       // key splits of pass 1
+constexpr int kMaxQSplits = 8;       // query splits of pass 2
+constexpr float kNoMax = -1e30f;     // finite stand-in for "no key seen yet"
 
-__device__ __forceinline__ float wave_half_swap(float v) { return __shfl_xor(v, 32, 64); }
+// Every staging point issues at most three direct loads per wave; waiting until at most two
+// are in flight leaves only (part of) the newest point outstanding.
+__device__ __forceinline__ void dma_wait_all_but_newest() { asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); }
+
+// Fetch the two 1-KB pieces of a 64-row tile this wave is responsible for; src(row) is the
+// global address of streamed row `row` of the tile.
+template <class Src>
+__device__ __forceinline__ void stage_rows(Src&& src, uint32_t lds_tile, int wave, int lane) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int row = (wave * 2 + i) * 4 + (lane >> 4);
+    const int chunk = k_chunk_pos(row, lane & 15);
+    dma_16B(src(row, i) + chunk * 8, lds_tile + (wave * 2 + i) * 1024);
+  }
+}
+
+// acc[b] = (32 streamed rows at `half`) x (stationary block b)^T, 16 products; after each
+// product epi(i) runs one sixteenth of the vector work of the previous half tile.
+template <class Epi>
+__device__ __forceinline__ void stream_phase(const lds_u8* half, const int (&a_off)[8],
+                                             const bf16x8 (&st)[2][8], f32x16 (&acc)[2], Epi&& epi) {
+  bf16x8 ring[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) ring[r] = lds_frag(half + a_off[r]);
+  f32x16 zero;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+#pragma unroll
+  for (int s = 0; s < 8; ++s) {
+    const bf16x8 a = ring[s & 3];
+    if (s + 4 < 8) ring[s & 3] = lds_frag(half + a_off[s + 4]);
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st[b][s], s == 0 ? zero : acc[b], 0, 0, 0);
+      epi(s * 2 + b);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
 
 // ---- pass 1: per-query (max, sum) over a slice of the keys ---------------------------------
-constexpr int kRowBN = 64;
-constexpr int kRowBM = 256;
+// S^T = K Q^T: a lane owns one query column of each stationary block and 16 of the 32 keys
+// of the half tile, and keeps its own running (max, sum) over the keys it sees; the two
+// halves of the wave are merged once at the end.
+struct RowState {
+  float m[2], l[2];
+};
+
+__device__ __forceinline__ void row_epilogue(int i, const f32x16 (&s)[2], RowState& st, float c) {
+  const int b = i >> 3, e = (i & 7) * 2;
+  if ((i & 7) == 0) {
+    float mx = fmaxf(s[b][0], s[b][1]);
+#pragma unroll
+    for (int k = 2; k < 16; k += 2) mx = fmaxf(mx, fmaxf(s[b][k], s[b][k + 1]));
+    const float m_new = fmaxf(st.m[b], mx * c);
+    st.l[b] *= __builtin_amdgcn_exp2f(st.m[b] - m_new);
+    st.m[b] = m_new;
+  }
+  st.l[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e], c, -st.m[b]));
+  st.l[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e + 1], c, -st.m[b]));
+}
+
+__device__ __forceinline__ void mask_keys(f32x16 (&s)[2], int k0, int Nk, int g) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+    if (k0 + (i >> 2) * 8 + g * 4 + (i & 3) >= Nk) {
+      s[0][i] = -INFINITY;
+      s[1][i] = -INFINITY;
+    }
+}
 
 __global__ __launch_bounds__(kThreads, 1) void score_rowpass_bf16(
-    const uint16_t* __restrict__ Qs, const int32_t* __restrict__ q_rows,
-    const uint16_t* __restrict__ K, float2* __restrict__ part, int Hq, int rep, int n_qs, int Nk, int64_t q_stride_h, int64_t k_stride_h, float c,
+    const uint16_t* __restrict__ Qs, const int32_t* __restrict__ q_rows, const uint16_t* __restrict__ K,
+    float2* __restrict__ part, int Hq, int rep, int n_qs, int Nk, int64_t q_stride_h, int64_t k_stride_h, float c,
     int n_row_tiles, int n_splits) {
-  __shared__ __align__(16) uint16_t ks[2][kRowBN * kKStride];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  extern __shared__ __align__(16) uint8_t smem_raw[];
+  lds_u8* smem = (lds_u8*)smem_raw;
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, g = lane >> 5;
-  const int split = blockIdx.y;
-  const int h = blockIdx.x / n_row_tiles, tile = blockIdx.x % n_row_tiles;
+  // logical order: split slowest, so the work-groups of one XCD stream the same keys
+  const int L = xcd_contiguous_index(blockIdx.x, gridDim.x);
+  const int split = L / (Hq * n_row_tiles);
+  const int h = (L / n_row_tiles) % Hq, tile = L % n_row_tiles;
   const int kvh = h / rep;
-  const int row0 = tile * kRowBM + wave * 64;
-  const bool active = row0 < n_qs;
+  const int row0 = tile * kBlockRows + wave * kWaveRows;
   const uint16_t* Qh = Qs + h * q_stride_h;
   const uint16_t* Kh = K + kvh * k_stride_h;
 
   bf16x8 qf[2][8];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    int row = min(row0 + qb * 32 + l32, n_qs - 1);
+  for (int b = 0; b < 2; ++b) {
+    int row = min(row0 + b * 32 + l32, n_qs - 1);
     if (q_rows) row = q_rows[row];
 #pragma unroll
     for (int s = 0; s < 8; ++s)
-      qf[qb][s] = *reinterpret_cast<const bf16x8*>(Qh + static_cast<int64_t>(row) * kD + s * 16 + g * 8);
+      qf[b][s] = *reinterpret_cast<const bf16x8*>(Qh + static_cast<int64_t>(row) * kD + s * 16 + g * 8);
   }
-  const int n_tiles = (Nk + kRowBN - 1) / kRowBN;
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[b][s]));
+
+  const int n_tiles = (Nk + kTileRows - 1) / kTileRows;
   const int per = (n_tiles + n_splits - 1) / n_splits;
   const int t_begin = min(split * per, n_tiles), t_end = min(t_begin + per, n_tiles);
+  const int n = t_end - t_begin;
+  if (n <= 0) {  // the host never launches an empty split; keep the partials defined anyway
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int row = row0 + b * 32 + l32;
+      if (g == 0 && row < n_qs) part[(static_cast<int64_t>(split) * Hq + h) * n_qs + row] = make_float2(kNoMax, 0.f);
+    }
+    return;
+  }
 
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
-  const int kc = threadIdx.x & 15, kr = threadIdx.x >> 4;
-  u32x4 regs[4];
-  auto load = [&](int t) {
+  int a_off[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int key = min(t * kRowBN + kr + 16 * i, Nk - 1);
-      regs[i] = *reinterpret_cast<const u32x4*>(Kh + static_cast<int64_t>(key) * kD + kc * 8);
-    }
+  for (int s = 0; s < 8; ++s) a_off[s] = l32 * kRowBytes + k_chunk_pos(l32, 2 * s + g) * 16;
+  auto stage = [&](int j) {  // tile j of this split (clamped: a repeat of the last tile is never read)
+    const int k0 = (t_begin + min(j, n - 1)) * kTileRows;
+    stage_rows([&](int row, int) { return Kh + static_cast<int64_t>(min(k0 + row, Nk - 1)) * kD; },
+               lds0 + (j & (kStages - 1)) * kTileBytes, wave, lane);
   };
-  auto store = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<u32x4*>(&ks[buf][(kr + 16 * i) * kKStride + kc * 8]) = regs[i];
-  };
-  if (t_begin < t_end) {
-    load(t_begin);
-    store(0);
-  }
+  auto slot = [&](int j) { return smem + (j & (kStages - 1)) * kTileBytes; };
+
+  RowState st;
+  st.m[0] = st.m[1] = kNoMax;
+  st.l[0] = st.l[1] = 0.f;
+  f32x16 sA[2], sB[2];
+
+  stage(0);
+  stage(1);
+  stage(2);
+  asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
   __syncthreads();
-  for (int t = t_begin; t < t_end; ++t) {
-    const int buf = (t - t_begin) & 1;
-    const bool more = t + 1 < t_end;
-    if (more) load(t + 1);
-    if (active) {
-      f32x16 acc[2][2];
+  stream_phase(slot(0), a_off, qf, sA, [](int) {});
+  for (int j = 0; j < n; ++j) {
+    const bool tail = (t_begin + j + 1) * kTileRows > Nk;  // only ever the last tile
+    dma_wait_all_but_newest();
+    __syncthreads();  // tile j+1 has landed everywhere; slot of tile j-1 is free
+    stage(j + 3);
+    if (tail) mask_keys(sA, (t_begin + j) * kTileRows, Nk, g);
+    stream_phase(slot(j) + 32 * kRowBytes, a_off, qf, sB, [&](int i) { row_epilogue(i, sA, st, c); });
+    if (tail) mask_keys(sB, (t_begin + j) * kTileRows + 32, Nk, g);
+    if (j + 1 < n) {
+      stream_phase(slot(j + 1), a_off, qf, sA, [&](int i) { row_epilogue(i, sB, st, c); });
+    } else {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acc[kb][qb][i] = 0.f;
-#pragma unroll
-      for (int s = 0; s < 8; ++s)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-          const bf16x8 kf =
-              *reinterpret_cast<const bf16x8*>(&ks[buf][(kb * 32 + l32) * kKStride + s * 16 + g * 8]);
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb)
-            acc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[qb][s], acc[kb][qb], 0, 0, 0);
-        }
-      const int k0 = t * kRowBN;
-      if (k0 + kRowBN > Nk) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            if (k0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3) >= Nk) {
-              acc[kb][0][i] = -INFINITY;
-              acc[kb][1][i] = -INFINITY;
-            }
-      }
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        float mx = acc[0][qb][0];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[kb][qb][i]);
-        mx = fmaxf(mx, wave_half_swap(mx));
-        const float m_new = fmaxf(m_run[qb], mx * c);
-        float psum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) psum += __builtin_amdgcn_exp2f(fmaf(acc[kb][qb][i], c, -m_new));
-        l_run[qb] = l_run[qb] * __builtin_amdgcn_exp2f(m_run[qb] - m_new) + psum;
-        m_run[qb] = m_new;
-      }
+      for (int i = 0; i < 16; ++i) row_epilogue(i, sB, st, c);
     }
-    if (more) store(buf ^ 1);
-    __syncthreads();
   }
-  if (!active) return;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no direct load may outlive the work-group
+
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const float l_tot = l_run[qb] + wave_half_swap(l_run[qb]);
-    const int row = row0 + qb * 32 + l32;
-    if (g == 0 && row < n_qs)
-      part[(static_cast<int64_t>(split) * Hq + h) * n_qs + row] = make_float2(m_run[qb], l_tot);
+  for (int b = 0; b < 2; ++b) {
+    const float m_o = wave_half_swap(st.m[b]), l_o = wave_half_swap(st.l[b]);
+    const float m = fmaxf(st.m[b], m_o);
+    const float l = st.l[b] * __builtin_amdgcn_exp2f(st.m[b] - m) + l_o * __builtin_amdgcn_exp2f(m_o - m);
+    const int row = row0 + b * 32 + l32;
+    if (g == 0 && row < n_qs) part[(static_cast<int64_t>(split) * Hq + h) * n_qs + row] = make_float2(m, l);
   }
 }
 
-// merge the per-split (max, sum) pairs in split order: lse2 = log2 sum_j 2^(c * s_j)
-__global__ void score_merge_rows(const float2* __restrict__ part, float* __restrict__ lse2,
-                                 int n_rows, int n_splits) {
+// Merge the per-split (max, sum) pairs in split order: lse2 = log2 sum_j 2^(c * s_j).  The
+// result is laid out [head][n_pad] with n_pad a multiple of the streamed tile; the padding
+// rows hold +inf so that they add nothing in pass 2.
+__global__ void score_merge_rows(const float2* __restrict__ part, float* __restrict__ lse2, int Hq, int n_qs,
+                                 int n_pad, int n_splits) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
-  if (r >= n_rows) return;
+  if (r >= Hq * n_pad) return;
+  const int h = r / n_pad, row = r % n_pad;
+  if (row >= n_qs) {
+    lse2[r] = INFINITY;
+    return;
+  }
+  const int64_t n_rows = static_cast<int64_t>(Hq) * n_qs, at = static_cast<int64_t>(h) * n_qs + row;
   float m = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) m = fmaxf(m, part[static_cast<int64_t>(s) * n_rows + r].x);
+  for (int s = 0; s < n_splits; ++s) m = fmaxf(m, part[s * n_rows + at].x);
   float l = 0.f;
   for (int s = 0; s < n_splits; ++s) {
-    const float2 p = part[static_cast<int64_t>(s) * n_rows + r];
+    const float2 p = part[s * n_rows + at];
     if (p.y > 0.f) l += p.y * exp2f(p.x - m);
   }
   lse2[r] = m + log2f(l);
 }
 
-// ---- pass 2: key-stationary column mass ---------------------------------------------------
-constexpr int kColKeys = 256;
-constexpr size_t kColSmem = kColKeys * kKStride * sizeof(uint16_t) + 4 * kColKeys * sizeof(float);
+// A caller's natural-log LSE [head][n_qs] -> the padded base-2 layout of pass 2.
+__global__ void score_import_lse(const float* __restrict__ lse, float* __restrict__ lse2, int Hq, int n_qs,
+                                 int n_pad) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= Hq * n_pad) return;
+  const int h = r / n_pad, row = r % n_pad;
+  lse2[r] = row < n_qs ? lse[static_cast<int64_t>(h) * n_qs + row] * 1.4426950408889634f : INFINITY;
+}
 
-__global__ __launch_bounds__(kThreads, 2) void score_colpass_bf16(
-    const uint16_t* __restrict__ Qs, const int32_t* __restrict__ q_rows,
-    const uint16_t* __restrict__ K, const float* __restrict__ lse, float lse_mul, float* __restrict__ score, int64_t score_stride_h, int rep, int n_qs, int Nk,
-    int64_t q_stride_h, int64_t k_stride_h, float c) {
+// ---- pass 2: column mass --------------------------------------------------------------------
+// S = Q K^T: a lane owns one key column of each stationary block and 16 of the 32 query rows
+// of the half tile.  The streamed operand is the list of (query head of the group, 64-row
+// tile) pairs; the normalisers of a tile travel through LDS beside it.
+__device__ __forceinline__ void col_epilogue(int i, const f32x16 (&s)[2], const float (&lq)[16], float (&colsum)[2],
+                                             float c) {
+  const int b = i >> 3, e = (i & 7) * 2;
+  colsum[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e], c, -lq[e]));
+  colsum[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e + 1], c, -lq[e + 1]));
+}
+
+__global__ __launch_bounds__(kThreads, 1) void score_colpass_bf16(
+    const uint16_t* __restrict__ Qs, const int32_t* __restrict__ q_rows, const uint16_t* __restrict__ K,
+    const float* __restrict__ lse2, float* __restrict__ out, int64_t out_stride_h, int64_t out_stride_split,
+    int Hkv, int rep, int n_qs, int Nk, int64_t q_stride_h, int64_t k_stride_h, float c, int n_key_blocks,
+    int n_qsplits) {
   extern __shared__ __align__(16) uint8_t smem_raw[];
-  uint16_t* ks = reinterpret_cast<uint16_t*>(smem_raw);
-  float* red = reinterpret_cast<float*>(smem_raw + kColKeys * kKStride * sizeof(uint16_t));
-
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  lds_u8* smem = (lds_u8*)smem_raw;
+  const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
+  constexpr int kLse0 = kStages * kTileBytes;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, g = lane >> 5;
-  const int kvh = blockIdx.y;
-  const int key0 = blockIdx.x * kColKeys;
+  // logical order: (kv head, query split) slowest, so the work-groups of one XCD stream the same queries
+  const int L = xcd_contiguous_index(blockIdx.x, gridDim.x);
+  const int kb = L % n_key_blocks, qsplit = (L / n_key_blocks) % n_qsplits, kvh = L / (n_key_blocks * n_qsplits);
+  const int key0 = kb * kBlockRows + wave * kWaveRows;
   const uint16_t* Kh = K + kvh * k_stride_h;
-  {
-    const int kc = threadIdx.x & 15, kr = threadIdx.x >> 4;
-#pragma unroll 4
-    for (int i = 0; i < kColKeys / 16; ++i) {
-      const int key = min(key0 + kr + 16 * i, Nk - 1);
-      *reinterpret_cast<u32x4*>(ks + (kr + 16 * i) * kKStride + kc * 8) =
-          *reinterpret_cast<const u32x4*>(Kh + static_cast<int64_t>(key) * kD + kc * 8);
-    }
+
+  bf16x8 kf[2][8];
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const int key = min(key0 + b * 32 + l32, Nk - 1);
+#pragma unroll
+    for (int s = 0; s < 8; ++s)
+      kf[b][s] = *reinterpret_cast<const bf16x8*>(Kh + static_cast<int64_t>(key) * kD + s * 16 + g * 8);
   }
-  __syncthreads();
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(kf[b][s]));
 
-  float colsum[8];
-#pragma unroll
-  for (int kb = 0; kb < 8; ++kb) colsum[kb] = 0.f;
+  const int tiles_per_head = (n_qs + kTileRows - 1) / kTileRows;
+  const int n_pad = tiles_per_head * kTileRows;
+  const int n_vt = rep * tiles_per_head;
+  const int per = (n_vt + n_qsplits - 1) / n_qsplits;
+  const int t_begin = min(qsplit * per, n_vt), t_end = min(t_begin + per, n_vt);
+  const int n = t_end - t_begin;
 
-  const int chunks_per_head = (n_qs + 63) / 64;
-  const int n_chunks = rep * chunks_per_head;
-  for (int chunk = wave; chunk < n_chunks; chunk += 4) {
-    const int h = kvh * rep + chunk / chunks_per_head;
-    const int row0 = (chunk % chunks_per_head) * 64;
-    const uint16_t* Qh = Qs + h * q_stride_h;
-    const float* lh = lse + static_cast<int64_t>(h) * n_qs;
-    bf16x8 qf[2][8];
-    float lq[2][16];
+  float colsum[2] = {0.f, 0.f};
+  if (n > 0) {
+    int a_off[8];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      int row = min(row0 + qb * 32 + l32, n_qs - 1);
-      if (q_rows) row = q_rows[row];
+    for (int s = 0; s < 8; ++s) a_off[s] = l32 * kRowBytes + k_chunk_pos(l32, 2 * s + g) * 16;
+    // source row (within its head) of the two pieces this lane fetches for tile j
+    auto src_rows = [&](int j, int (&rows)[2]) {
+      const int vt = t_begin + min(j, n - 1);
+      const int r0 = (vt % tiles_per_head) * kTileRows;
 #pragma unroll
-      for (int s = 0; s < 8; ++s)
-        qf[qb][s] = *reinterpret_cast<const bf16x8*>(Qh + static_cast<int64_t>(row) * kD + s * 16 + g * 8);
+      for (int i = 0; i < 2; ++i) {
+        const int row = min(r0 + (wave * 2 + i) * 4 + (lane >> 4), n_qs - 1);
+        rows[i] = q_rows ? q_rows[row] : row;
+      }
+    };
+    auto stage = [&](int j, const int (&rows)[2]) {
+      const int vt = t_begin + min(j, n - 1);
+      const int h = kvh * rep + vt / tiles_per_head;
+      const uint16_t* Qh = Qs + h * q_stride_h;
+      stage_rows([&](int, int i) { return Qh + static_cast<int64_t>(rows[i]) * kD; },
+                 lds0 + (j & (kStages - 1)) * kTileBytes, wave, lane);
+      if (wave == 0)
+        dma_4B(lse2 + static_cast<int64_t>(h) * n_pad + (vt % tiles_per_head) * kTileRows + lane,
+               lds0 + kLse0 + (j & (kStages - 1)) * kLseSlotBytes);
+    };
+    auto slot = [&](int j) { return smem + (j & (kStages - 1)) * kTileBytes; };
+    // normalisers of the 16 rows this lane holds in half `half` of tile j
+    auto load_lq = [&](int j, int half, float (&lq)[16]) {
+      const lds_u8* base = smem + kLse0 + (j & (kStages - 1)) * kLseSlotBytes + (half * 32 + g * 4) * 4;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int r = row0 + qb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-        lq[qb][i] = r < n_qs ? lh[r] * lse_mul : INFINITY;  // rows past the end add nothing
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 v = *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(base + q * 32);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) lq[q * 4 + e] = v[e];
+      }
+    };
+
+    f32x16 sA[2], sB[2];
+    float lq[16];
+    int rows[2];
+    src_rows(0, rows);
+    stage(0, rows);
+    src_rows(1, rows);
+    stage(1, rows);
+    src_rows(2, rows);
+    stage(2, rows);
+    src_rows(3, rows);
+    asm volatile("s_waitcnt vmcnt(4)" ::: "memory");  // at least the first tile's pieces
+    __syncthreads();
+    stream_phase(slot(0), a_off, kf, sA, [](int) {});
+    for (int j = 0; j < n; ++j) {
+      dma_wait_all_but_newest();
+      __syncthreads();  // tile j+1 has landed everywhere; slot of tile j-1 is free
+      stage(j + 3, rows);
+      src_rows(j + 4, rows);
+      load_lq(j, 0, lq);
+      stream_phase(slot(j) + 32 * kRowBytes, a_off, kf, sB, [&](int i) { col_epilogue(i, sA, lq, colsum, c); });
+      load_lq(j, 1, lq);
+      if (j + 1 < n) {
+        stream_phase(slot(j + 1), a_off, kf, sA, [&](int i) { col_epilogue(i, sB, lq, colsum, c); });
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) col_epilogue(i, sB, lq, colsum, c);
       }
     }
-#pragma unroll
-    for (int kb = 0; kb < 8; ++kb) {
-      f32x16 acc[2];
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[qb][i] = 0.f;
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        const bf16x8 kf =
-            *reinterpret_cast<const bf16x8*>(ks + (kb * 32 + l32) * kKStride + s * 16 + g * 8);
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
-          acc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[qb][s], kf, acc[qb], 0, 0, 0);
-      }
-      float sum = 0.f;
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(acc[qb][i], c, -lq[qb][i]));
-      colsum[kb] += sum;
-    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no direct load may outlive the work-group
   }
 #pragma unroll
-  for (int kb = 0; kb < 8; ++kb) {
-    const float v = colsum[kb] + wave_half_swap(colsum[kb]);
-    if (g == 0) red[wave * kColKeys + kb * 32 + l32] = v;
-  }
-  __syncthreads();
-  const int key = key0 + threadIdx.x;
-  if (key < Nk) {
-    const int t = threadIdx.x;
-    score[kvh * score_stride_h + key] =
-        ((red[t] + red[kColKeys + t]) + red[2 * kColKeys + t]) + red[3 * kColKeys + t];
+  for (int b = 0; b < 2; ++b) {
+    const float v = colsum[b] + wave_half_swap(colsum[b]);
+    const int key = key0 + b * 32 + l32;
+    if (g == 0 && key < Nk) out[qsplit * out_stride_split + kvh * out_stride_h + key] = v;
   }
 }
 
-// sum the per-KV-head mass over heads, head 0 first
-__global__ void score_share_heads(const float* __restrict__ per_head, float* __restrict__ out,
-                                  int Hkv, int Nk) {
+// out[h][j] = sum over parts p of part[p][h][j] (p ascending); with share_heads the heads are
+// summed too, head 0 first, into out[j].
+__global__ void score_reduce(const float* __restrict__ part, float* __restrict__ out, int64_t out_stride_h,
+                             int n_parts, int Hkv, int Nk, int share_heads) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= Nk) return;
-  float s = 0.f;
-  for (int g = 0; g < Hkv; ++g) s += per_head[static_cast<int64_t>(g) * Nk + j];
-  out[j] = s;
+  const int64_t split_stride = static_cast<int64_t>(Hkv) * Nk;
+  if (share_heads) {
+    float s = 0.f;
+    for (int h = 0; h < Hkv; ++h) {
+      float sh = 0.f;
+      for (int p = 0; p < n_parts; ++p) sh += part[p * split_stride + static_cast<int64_t>(h) * Nk + j];
+      s += sh;
+    }
+    out[j] = s;
+  } else {
+    const int h = blockIdx.y;
+    float sh = 0.f;
+    for (int p = 0; p < n_parts; ++p) sh += part[p * split_stride + static_cast<int64_t>(h) * Nk + j];
+    out[h * out_stride_h + j] = sh;
+  }
 }
 
 // ---- fp32 correctness tier ------------------------------------------------------------------
@@ -347,20 +475,47 @@ __global__ __launch_bounds__(64) void score_colpass_f32(const float* __restrict_
 }
 
 struct WsLayout {
-  size_t lse_off, part_off, heads_off, total;
+  size_t lse_off, part_off, col_off, total;
 };
 
-WsLayout ws_layout(int Hq, int Hkv, int n_qs, int Nk, int share_heads) {
+int padded_rows(int n_qs) { return ceil_div(n_qs, kTileRows) * kTileRows; }
+
+WsLayout ws_layout(int Hq, int Hkv, int n_qs, int Nk, int /*share_heads*/) {
   WsLayout w;
   size_t at = 0;
   w.lse_off = at;
-  at += align_up(sizeof(float) * static_cast<size_t>(Hq) * n_qs, 256);
+  at += align_up(sizeof(float) * static_cast<size_t>(Hq) * padded_rows(n_qs), 256);
   w.part_off = at;
   at += align_up(sizeof(float2) * static_cast<size_t>(kMaxSplits) * Hq * n_qs, 256);
-  w.heads_off = at;
-  if (share_heads) at += align_up(sizeof(float) * static_cast<size_t>(Hkv) * Nk, 256);
+  w.col_off = at;
+  at += align_up(sizeof(float) * static_cast<size_t>(kMaxQSplits) * Hkv * Nk, 256);
   w.total = at;
   return w;
+}
+
+// Number of ways to split the streamed axis (n_tiles tiles) so that `base` x splits
+// work-groups fill the 256 compute units in whole rounds without making a work-group's
+// share so short that its three-tile prologue shows.
+int choose_splits(int base, int n_tiles, int max_splits) {
+  int best = 1;
+  double best_score = -1.0;
+  for (int s = 1; s <= std::min(max_splits, n_tiles); ++s) {
+    const int blocks = base * s, rounds = ceil_div(blocks, 256), per = ceil_div(n_tiles, s);
+    const double score = static_cast<double>(blocks) / (rounds * 256.0) * per / (per + 2.0);
+    if (score > best_score * 1.001) {
+      best_score = score;
+      best = s;
+    }
+  }
+  return best;
+}
+
+template <class Kernel>
+int allow_lds(Kernel kernel, size_t bytes) {
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+  if (e != hipSuccess) PC_FAIL(PC_ERR_HIP, "pc_score: LDS attribute: %s", hipGetErrorString(e));
+  return PC_OK;
 }
 
 }  // namespace
@@ -396,8 +551,7 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
   uint8_t* wsb = static_cast<uint8_t*>(ws);
   float* ws_lse = reinterpret_cast<float*>(wsb + lay.lse_off);
   float2* ws_part = reinterpret_cast<float2*>(wsb + lay.part_off);
-  float* per_head = share_heads ? reinterpret_cast<float*>(wsb + lay.heads_off) : score;
-  const int64_t per_head_stride = share_heads ? Nk : score_stride_h;
+  float* ws_col = reinterpret_cast<float*>(wsb + lay.col_off);
   const int rep = Hq / Hkv;
 
   if (dtype == PC_BF16) {
@@ -405,38 +559,45 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
     const uintptr_t al = reinterpret_cast<uintptr_t>(Qs) | reinterpret_cast<uintptr_t>(K);
     PC_REQUIRE(al % 16 == 0 && q_stride_h % 8 == 0 && k_stride_h % 8 == 0, PC_ERR_SHAPE,
                "pc_score: bf16 tensors and head strides must be 16-byte aligned");
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (int rc = allow_lds(score_rowpass_bf16, kRowSmem)) return rc;
+      if (int rc = allow_lds(score_colpass_bf16, kColSmem)) return rc;
+      attr_set = true;
+    }
     const float c = scale * 1.4426950408889634f;
-    const float* lse_in = lse;
-    float lse_mul = 1.4426950408889634f;  // caller's natural-log LSE -> base 2
+    const int n_pad = padded_rows(n_qs);
     if (lse == nullptr) {
-      const int n_row_tiles = ceil_div(n_qs, kRowBM);
-      const int n_tiles = ceil_div(Nk, kRowBN);
-      int n_splits = ceil_div(1024, n_row_tiles * Hq);
-      n_splits = std::max(1, std::min(std::min(n_splits, kMaxSplits), n_tiles));
-      score_rowpass_bf16<<<dim3(n_row_tiles * Hq, n_splits), kThreads, 0, s>>>(
+      const int n_row_tiles = ceil_div(n_qs, kBlockRows);
+      const int n_splits = choose_splits(n_row_tiles * Hq, ceil_div(Nk, kTileRows), kMaxSplits);
+      score_rowpass_bf16<<<n_row_tiles * Hq * n_splits, kThreads, kRowSmem, s>>>(
           static_cast<const uint16_t*>(Qs), q_rows, static_cast<const uint16_t*>(K), ws_part, Hq, rep, n_qs, Nk,
           q_stride_h, k_stride_h, c, n_row_tiles, n_splits);
       PC_CHECK_LAUNCH("pc_score row pass");
-      const int n_rows = Hq * n_qs;
-      score_merge_rows<<<ceil_div(n_rows, 256), 256, 0, s>>>(ws_part, ws_lse, n_rows, n_splits);
+      score_merge_rows<<<ceil_div(Hq * n_pad, 256), 256, 0, s>>>(ws_part, ws_lse, Hq, n_qs, n_pad, n_splits);
       PC_CHECK_LAUNCH("pc_score merge");
-      lse_in = ws_lse;
-      lse_mul = 1.f;
+    } else {
+      score_import_lse<<<ceil_div(Hq * n_pad, 256), 256, 0, s>>>(lse, ws_lse, Hq, n_qs, n_pad);
+      PC_CHECK_LAUNCH("pc_score lse import");
     }
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(score_colpass_bf16),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         static_cast<int>(kColSmem));
-      if (e != hipSuccess) PC_FAIL(PC_ERR_HIP, "pc_score: LDS attribute: %s", hipGetErrorString(e));
-      attr_set = true;
-    }
-    score_colpass_bf16<<<dim3(ceil_div(Nk, kColKeys), Hkv), kThreads, kColSmem, s>>>(
-        static_cast<const uint16_t*>(Qs), q_rows, static_cast<const uint16_t*>(K), lse_in, lse_mul, per_head,
-        per_head_stride, rep, n_qs, Nk, q_stride_h, k_stride_h, c);
+    const int n_key_blocks = ceil_div(Nk, kBlockRows);
+    const int n_qsplits = choose_splits(n_key_blocks * Hkv, rep * (n_pad / kTileRows), kMaxQSplits);
+    const bool direct = n_qsplits == 1 && !share_heads;
+    score_colpass_bf16<<<n_key_blocks * Hkv * n_qsplits, kThreads, kColSmem, s>>>(
+        static_cast<const uint16_t*>(Qs), q_rows, static_cast<const uint16_t*>(K), ws_lse, direct ? score : ws_col,
+        direct ? score_stride_h : Nk, static_cast<int64_t>(Hkv) * Nk, Hkv, rep, n_qs, Nk, q_stride_h, k_stride_h, c,
+        n_key_blocks, n_qsplits);
     PC_CHECK_LAUNCH("pc_score column pass");
+    if (!direct) {
+      score_reduce<<<dim3(ceil_div(Nk, 256), share_heads ? 1 : Hkv), 256, 0, s>>>(ws_col, score, score_stride_h,
+                                                                                  n_qsplits, Hkv, Nk, share_heads);
+      PC_CHECK_LAUNCH("pc_score reduce");
+    }
+    return PC_OK;
   } else {
     PC_REQUIRE(D == 64 || D == 128, PC_ERR_UNSUPPORTED, "pc_score: fp32 tier needs D=64 or 128, got %d", D);
+    float* per_head = share_heads ? ws_col : score;
+    const int64_t per_head_stride = share_heads ? Nk : score_stride_h;
     const float* q = static_cast<const float*>(Qs);
     const float* k = static_cast<const float*>(K);
     const float* lse_in = lse;
@@ -457,10 +618,10 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
       score_colpass_f32<128><<<grid, 64, 0, s>>>(q, q_rows, k, lse_in, per_head, per_head_stride, rep, n_qs, Nk,
                                                    q_stride_h, k_stride_h, scale);
     PC_CHECK_LAUNCH("pc_score column pass");
-  }
-  if (share_heads) {
-    score_share_heads<<<ceil_div(Nk, 256), 256, 0, s>>>(per_head, score, Hkv, Nk);
-    PC_CHECK_LAUNCH("pc_score head sum");
+    if (share_heads) {
+      score_reduce<<<ceil_div(Nk, 256), 256, 0, s>>>(ws_col, score, score_stride_h, 1, Hkv, Nk, 1);
+      PC_CHECK_LAUNCH("pc_score head sum");
+    }
   }
   return PC_OK;
 }
