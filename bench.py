@@ -21,6 +21,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+# Bytes one launch moved between L2 and the memory fabric, from the rocprofv3 --pmc runs of
+# this script whose summaries are committed under profiles/ (FETCH_SIZE counter x 1.9998 + WRITE_SIZE
+# x 1.0000, the factors a plain 256 MiB device copy in the same runs gave).  They hold for the
+# default workload only and are reported, not re-measured, here.
+TRAFFIC_ATTN_F24_PACKED_BYTES = int((67164.4 * 1.9998 + 16128.0) * 1024)
+TRAFFIC_COMPACT_F48_G085_BYTES = int((41670.6 * 1.9998 + 76945.4) * 1024)   # per layer, in place
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
@@ -42,6 +48,12 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true", help="per-frame dense vs packed, frames 1..48")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-f48", action="store_true", help="skip the frame-48 compaction / dense legs")
+    ap.add_argument("--no-dense", action="store_true",
+                    help="skip the dense frame-24 comparison call, so that a profile of this command "
+                         "sees pc_frame_attn at the packed shape only")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="first run three plain 256 MiB device copies: the known-size dispatches that "
+                         "calibrate FETCH_SIZE / WRITE_SIZE in a counter run of this same command")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
@@ -57,6 +69,13 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     pk.lib()   # fail loudly if the HIP library is missing
+    if args.copy_probe:
+        src = torch.arange(1 << 26, dtype=torch.int32, device=dev)   # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     def up(a, bf=True):
         t = torch.from_numpy(np.ascontiguousarray(a))
@@ -127,7 +146,7 @@ def main() -> int:
                              pk.pc_rope3d(k_new, pos_new, w.sections, w.base)), 10)
     score_ms = timed(lambda: pk.pc_score(Q, K, Nk, w.scale, score=score, ws=ws_s, q_rows=rows), 10)
     compact_ms = timed(lambda: pk.pc_compact(K, V, pos, score, w.segments, budgets, out=(Kp, Vp, pp), ws=ws_c), 10)
-    dense_ms = timed(lambda: pk.pc_frame_attn(Q, K, V, Nk, w.scale, O=O), 3)
+    dense_ms = None if args.no_dense else timed(lambda: pk.pc_frame_attn(Q, K, V, Nk, w.scale, O=O), 3)
     score_flops = 2.0 * 2.0 * D * rows.numel() * Hq * Nk          # two QK^T passes
     out = {
         "metric": "packed frame-attn ms/layer + TFLOP/s (% MFMA peak); compaction GB/s at 48 frames",
@@ -141,16 +160,18 @@ def main() -> int:
                    "Nq": Nq, "Nk_dense": Nk, "Nk_packed": nk_packed, "gamma": w.gamma, "b_min": w.b_min,
                    "score_queries": int(rows.numel())},
         "attn_packed_ms_per_layer": round(attn_ms, 4),
-        "attn_dense_ms_per_layer": round(dense_ms, 4),
-        "attn_dense_tflops": round(attn_flops(Hq, Nq, Nk, D) / (dense_ms * 1e-3) / 1e12, 2),
-        "dense_vs_packed_speedup_f24": round(dense_ms / attn_ms, 3),
-        "dense_vs_packed_path_speedup_f24": round(dense_ms / ms_per_step, 3),
+        "attn_dense_ms_per_layer": dense_ms and round(dense_ms, 4),
+        "attn_dense_tflops": dense_ms and round(attn_flops(Hq, Nq, Nk, D) / (dense_ms * 1e-3) / 1e12, 2),
+        "dense_vs_packed_speedup_f24": dense_ms and round(dense_ms / attn_ms, 3),
+        "dense_vs_packed_path_speedup_f24": dense_ms and round(dense_ms / ms_per_step, 3),
         "step_breakdown_ms": {"rope3d": round(rope_ms, 4), "score": round(score_ms, 4),
                               "compact": round(compact_ms, 4), "frame_attn": round(attn_ms, 4)},
         "score_tflops": round(score_flops / (score_ms * 1e-3) / 1e12, 2),
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": TRAFFIC_ATTN_F24_PACKED_BYTES, "traffic_unit": "bytes per launch",
+                     "algorithmic_bytes": int(2 * D * (2 * Hq * Nq + 2 * Hkv * nk_packed))},
     }
     del Q, Q0, K, V, Kp, Vp, pp, O, score, pos
 
@@ -201,7 +222,8 @@ def main() -> int:
         out["compaction_f48_in_place"] = comp
         out["roofline_compact"] = {"bound": "hbm", "kernel": "pc_compact = select_block_kernel + gather_kernel, in place, gamma 0.85, 28 layers",
                                    "achieved": comp["0.85"]["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                   "frac": comp["0.85"]["frac_hbm"], "traffic": None}
+                                   "frac": comp["0.85"]["frac_hbm"],
+                                   "traffic": TRAFFIC_COMPACT_F48_G085_BYTES, "traffic_unit": "bytes per layer"}
         out["frame48"] = {"Nk_dense": Nk48, "Nk_packed": nk48_packed, "attn_dense_ms": round(dense48_ms, 4),
                           "attn_packed_ms": round(packed48_ms, 4),
                           "attn_packed_tflops": round(attn_flops(Hq, Nq, nk48_packed, D) / (packed48_ms * 1e-3) / 1e12, 2),
