@@ -1,0 +1,123 @@
+"""GPU parity at the full sizes and in the launch configuration that bench.py times:
+16 query heads, 4 KV heads, D = 128, 48x84 tokens per frame, 256 text tokens, at frames
+2, 12, 24 and 48 (up to 193,792 dense keys), gamma = 0.85 with a 512-token minimum quota.
+
+Each step is compared with the fp64 oracle on identical input bits:
+  * pc_rope3d on the whole new frame (all elements);
+  * pc_score over all keys with the 512 strided scoring rows (all elements);
+  * the selected index sets (bit-exact outside the 1e-6 score band), the gathered rows
+    and carried positions (bit-exact), out of place as in the frame-24 step and in place
+    as in the frame-48 compaction runs, for gamma in {0.7, 0.85, 0.95};
+  * pc_frame_attn, packed and dense, on 64 sampled query rows per head over all keys
+    (max |err| <= 2e-2, mean |err| <= 2e-3), and its log-sum-exp output.
+The steps after the rotation read the ORACLE's rotated bits, so that every step is judged on
+inputs identical to the oracle's; the chained device path is covered at reduced size in
+test_gpu_parity.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_2601_04359_amd as pk
+from paper_2601_04359_amd import synth
+
+from test_gpu_parity import BAND, DEV, check_selection, dev, host
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+N_SAMPLE_ROWS = 64
+
+
+def _budgets(w, gamma):
+    b = pk.pc_budget(pk.PC_BUDGET_POW, w.n_frame, w.n_past, gamma, w.b_min)
+    assert b == orc.budget_pow(w.n_frame, w.n_past, gamma, w.b_min)
+    return pk.segment_budgets(w.segments, b)
+
+
+@pytest.mark.parametrize("frame", [2, 12, 24, 48])
+def test_full_size_frame(frame):
+    w = synth.config2(seed=1000, n_past=frame - 1)
+    Hq, Hkv, Nk, Nq = w.Hq, w.Hkv, w.Nk, w.Nq
+    newest = w.segments[-1]
+    a, n_new = newest[0], newest[1]
+    print(f"frame {frame}: Nk={Nk}", flush=True)
+
+    # ---- a1: rotation of the new frame's queries and of the newest cached frame's keys
+    Qd, Kd = dev(w.Q, "bf16"), dev(w.K, "bf16")
+    pk.pc_rope3d(Qd, dev(w.pos_q, None), w.sections, w.base)
+    kn = Kd[:, a:a + n_new]
+    pk.pc_rope3d(kn, dev(w.pos_k[a:a + n_new], None), w.sections, w.base)
+    q_rot = orc.rope3d(w.Q, w.pos_q, w.sections, w.base)
+    k_rot = orc.rope3d(w.K[:, a:a + n_new], w.pos_k[a:a + n_new], w.sections, w.base)
+    for got, want in ((host(Qd), q_rot), (host(kn), k_rot)):
+        assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-6)
+    assert torch.equal(Kd[:, :a], dev(w.K[:, :a], "bf16")), "rows outside the new frame must not change"
+    del Qd, Kd, kn
+
+    # the oracle's rotated bits feed every later step on both sides
+    Qo = orc.round_to_bf16(q_rot)
+    Ko = w.K.astype(np.float64)
+    Ko[:, a:a + n_new] = orc.round_to_bf16(k_rot)
+    Vo = w.V.astype(np.float64)
+    Q, K, V = dev(Qo.astype(np.float32), "bf16"), dev(Ko.astype(np.float32), "bf16"), dev(w.V, "bf16")
+    assert np.array_equal(host(Q), Qo) and np.array_equal(host(K[:, a:]), Ko[:, a:])
+    pos_host = np.broadcast_to(w.pos_k[None], (Hkv, Nk, 3)).copy()
+    pos = dev(pos_host, None)
+
+    # ---- a2: importance of every key
+    rows = dev(w.score_rows.astype(np.int32), None)
+    sc = pk.pc_score(Q, K, Nk, w.scale, q_rows=rows)
+    sco = orc.score(Qo[:, w.score_rows], Ko, w.scale)
+    got = host(sc).astype(np.float64)
+    err = np.abs(got - sco)
+    assert np.all(err <= 2e-7 + 2e-5 * sco), (err.max(), (err / (sco + 1e-30)).max())
+    np.testing.assert_allclose(got.sum(1), w.score_rows.size * (Hq // Hkv), rtol=1e-5)
+    print("score ok", flush=True)
+
+    # ---- a3..a5: budgets, selection, gather; out of place and in place
+    kept = {}
+    for gamma in (0.85, 0.7, 0.95):
+        budgets = _budgets(w, gamma)
+        segs_want = orc.packed_segments(w.segments, budgets)
+        nk_want = segs_want[-1][0] + segs_want[-1][1]
+        Kp, Vp = torch.empty((Hkv, nk_want, w.D), dtype=K.dtype, device=DEV), torch.empty(
+            (Hkv, nk_want, w.D), dtype=K.dtype, device=DEV)
+        pp = torch.empty((Hkv, nk_want, 3), dtype=torch.int32, device=DEV)
+        idx = torch.empty((Hkv, nk_want), dtype=torch.int32, device=DEV)
+        segs, nk = pk.pc_compact(K, V, pos, sc, w.segments, budgets, out=(Kp, Vp, pp), idx=idx)
+        assert nk == nk_want and segs == segs_want
+        ig = host(idx)
+        check_selection(ig, sco, w.segments, budgets, band=BAND)
+        for h in range(Hkv):
+            sel = idx[h].long()
+            assert torch.equal(Kp[h], K[h].index_select(0, sel))
+            assert torch.equal(Vp[h], V[h].index_select(0, sel))
+            assert np.array_equal(host(pp[h]), w.pos_k[ig[h]])
+        # in place on a copy of the cache: the same rows must end up in the packed prefix
+        K2, V2, p2 = K.clone(), V.clone(), pos.clone()
+        idx2 = torch.empty_like(idx)
+        segs2, nk2 = pk.pc_compact(K2, V2, p2, sc, w.segments, budgets, idx=idx2)
+        assert nk2 == nk and segs2 == segs and torch.equal(idx2, idx)
+        assert torch.equal(K2[:, :nk], Kp) and torch.equal(V2[:, :nk], Vp) and torch.equal(p2[:, :nk], pp)
+        del K2, V2, p2
+        if gamma == w.gamma:
+            kept = {"K": Kp, "V": Vp, "idx": ig, "nk": nk}
+        print(f"compact gamma={gamma} ok, Nk_packed={nk}", flush=True)
+
+    # ---- a6: attention over the kept keys, and over the dense cache, on sampled query rows
+    rs = synth.strided_rows(Nq, N_SAMPLE_ROWS)
+    ig, nk = kept["idx"], kept["nk"]
+    lse = torch.empty((Hq, Nq), dtype=torch.float32, device=DEV)
+    O = pk.pc_frame_attn(Q, kept["K"], kept["V"], nk, w.scale, lse=lse)
+    Kk = np.stack([Ko[g][ig[g]] for g in range(Hkv)])
+    Vk = np.stack([Vo[g][ig[g]] for g in range(Hkv)])
+    Ow, Lw = orc.frame_attn(Qo[:, rs], Kk, Vk, w.scale)
+    err = np.abs(host(O)[:, rs].astype(np.float64) - Ow)
+    assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
+    assert np.abs(host(lse)[:, rs] - Lw).max() <= 1e-3
+    O = pk.pc_frame_attn(Q, K, V, Nk, w.scale, lse=lse)
+    Ow, Lw = orc.frame_attn(Qo[:, rs], Ko, Vo, w.scale)
+    err = np.abs(host(O)[:, rs].astype(np.float64) - Ow)
+    assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
+    assert np.abs(host(lse)[:, rs] - Lw).max() <= 1e-3
