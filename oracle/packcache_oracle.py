@@ -34,7 +34,7 @@ __all__ = [
     "budget_pow", "budget_norm", "budget_half", "budget_slide",
     "rope_angles", "rope3d",
     "logits", "softmax_rows", "score", "select_topk", "compact", "packed_segments",
-    "frame_attn", "frame_attn_bruteforce", "score_bruteforce",
+    "frame_attn", "frame_attn_bruteforce", "score_bruteforce", "rolling_rollout",
 ]
 
 SEG_TEXT, SEG_COND, SEG_FRAME, SEG_SELF = 0, 1, 2, 3
@@ -255,6 +255,57 @@ def compact(K, V, pos, sc, segments, budgets, share_heads: bool = False):
     Vp = np.stack([V[g][idx[0 if share_heads else g]] for g in range(hkv)])
     pp = np.stack([pos[h][idx[h]] for h in range(hsel)])
     return Kp, Vp, pp, idx, packed_segments(segments, budgets)
+
+
+# --------------------------------------------------------------------------------------
+# rolling rollout (Sec. 3.4: every retained frame is re-packed at every step under the same
+# allocation rule, so eviction is irreversible: the candidates of a frame at step f are
+# its survivors of step f - 1)
+# --------------------------------------------------------------------------------------
+def rolling_rollout(anchor_K, anchor_V, anchor_pos, anchor_segments, frames, queries, scale: float,
+                    budget_fn, score_rows=None, share_heads: bool = False):
+    """Generate-time cache management over several frame steps.
+
+    anchor_K, anchor_V [Hkv][A][D], anchor_pos [A][3], anchor_segments: the always-kept
+    text / conditioning-image rows (keys already rotated).
+    frames[j] = (K_j, V_j, pos_j): keys (rotated), values and (t, h, w) of generated frame
+    j + 1, appended whole to the cache before the step that generates frame j + 2.
+    queries[i]: rotated queries [Hq][Nq][D] of step i + 1, which sees frames 1..i.
+    budget_fn(n_past) -> per-distance budgets, entry d - 1 for distance d.
+    Each step: append the newest frame, score all cached keys with the scoring rows of the
+    step's queries, keep the per-frame top-budget keys (anchors whole), attend over what
+    is left.  Returns one dict per step: K, V, pos, segments (the packed cache the step
+    attended over), O and lse."""
+    hkv = np.asarray(anchor_K).shape[0]
+    hsel = 1 if share_heads else hkv
+    K, V = f64(anchor_K), f64(anchor_V)
+    pos = np.broadcast_to(np.asarray(anchor_pos)[None], (hsel,) + np.asarray(anchor_pos).shape).copy()
+    segments = list(anchor_segments)
+    steps = []
+    for i, Q in enumerate(queries):
+        if i >= 1:
+            Kf, Vf, pf = frames[i - 1]
+            at = K.shape[1]
+            K = np.concatenate([K, f64(Kf)], axis=1)
+            V = np.concatenate([V, f64(Vf)], axis=1)
+            pos = np.concatenate([pos, np.broadcast_to(np.asarray(pf)[None], (hsel,) + np.asarray(pf).shape)], axis=1)
+            segments.append((at, np.asarray(Kf).shape[1], SEG_FRAME, i))
+        Q = f64(Q)
+        n_past = sum(1 for s in segments if s[2] == SEG_FRAME)
+        per_distance = budget_fn(n_past)
+        # the newest past frame is the LAST frame segment: distance 1
+        budgets, d = [], n_past
+        for (_, length, kind, _) in segments:
+            if kind == SEG_FRAME:
+                budgets.append(per_distance[d - 1])
+                d -= 1
+            else:
+                budgets.append(length)
+        sc = score(Q if score_rows is None else Q[:, score_rows], K, scale, share_heads=share_heads)
+        K, V, pos, _, segments = compact(K, V, pos, sc, segments, budgets, share_heads=share_heads)
+        O, lse = frame_attn(Q, K, V, scale)
+        steps.append({"K": K, "V": V, "pos": pos, "segments": list(segments), "O": O, "lse": lse})
+    return steps
 
 
 # --------------------------------------------------------------------------------------

@@ -184,3 +184,89 @@ def midsize(seed: int = 7, dtype: str = "bf16", n_past: int = 6, hq: int = 8, hk
     ragged (252 tokens per frame, 40 text tokens) so tiles have tails."""
     return frame_layer("mid", seed, hq, hkv, 128, n_text, gh, gw, n_past, gamma, b_min, (32, 48, 48),
                        n_score=100, dtype=dtype)
+
+
+# --------------------------------------------------------------------------------------
+# rolling rollout: one layer's stream of frames
+# --------------------------------------------------------------------------------------
+@dataclass
+class RollingCase:
+    """Inputs of a multi-step rollout of one layer.  Keys and queries are UN-rotated;
+    frames[j] belongs to generated frame j + 1, queries[i] to the step that generates
+    frame i + 1 and sees frames 1..i."""
+    dtype: str
+    Hq: int
+    Hkv: int
+    D: int
+    n_text: int
+    gh: int
+    gw: int
+    sections: tuple
+    base: float
+    anchor_K: np.ndarray
+    anchor_V: np.ndarray
+    anchor_pos: np.ndarray
+    anchor_segments: list
+    frames: list            # (K [Hkv][n][D], V, pos [n][3])
+    queries: list           # Q [Hq][n][D]
+    query_pos: list         # [n][3] per step
+    score_rows: np.ndarray
+
+    @property
+    def n_frame(self) -> int:
+        return self.gh * self.gw
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / float(np.sqrt(self.D))
+
+
+def rolling_directions(rng, hkv: int, d: int, n_dir: int, sections) -> np.ndarray:
+    """[Hkv][n_dir][D] unit vectors on the slowest rotary pairs (direction 0: anchors,
+    direction j: generated frame j)."""
+    lf = low_frequency_dims(sections)
+    u = np.zeros((hkv, n_dir, d), np.float32)
+    u[:, :, lf] = rng.standard_normal((hkv, n_dir, lf.size)).astype(np.float32)
+    u /= np.linalg.norm(u, axis=2, keepdims=True)
+    return u
+
+
+def query_direction(u: np.ndarray, step: int) -> np.ndarray:
+    """Mean direction of the queries of `step` (1-based): anchors at full weight, frame j
+    at 0.9^(step - j), so that the mean logit of a cached frame decays with its age."""
+    w = u[:, 0].copy()
+    for j in range(1, step):
+        w += np.float32(0.9 ** (step - j)) * u[:, j]
+    return w
+
+
+def rolling_case(seed: int = 11, n_steps: int = 6, hq: int = 8, hkv: int = 2, d: int = 128, n_text: int = 40,
+                 gh: int = 12, gw: int = 21, sections=(32, 48, 48), n_score: int = 100,
+                 dtype: str = "bf16") -> RollingCase:
+    """A rollout of n_steps frame steps: V ~ N(0,1); K ~ N(0,1) + 0.5 u_0 for the anchors
+    and + 0.3 u_j for generated frame j; Q of step f ~ N(0,1) + sqrt(D) * (u_0 + sum_j
+    0.9^(f-j) u_j).  The directions u live on the slowest rotary pairs, so the structure
+    survives the rotation; they are random, not orthogonal, so frames leak a little into
+    each other's mean logit."""
+    rng = np.random.default_rng(seed)
+    n = gh * gw
+    rep = hq // hkv
+    u = rolling_directions(rng, hkv, d, n_steps + 1, sections)
+    rnd = to_bf16 if dtype == "bf16" else (lambda a: a)
+    n_anchor = n_text + n
+    aK = rng.standard_normal((hkv, n_anchor, d), dtype=np.float32) + np.float32(0.5) * u[:, 0][:, None, :]
+    aV = rng.standard_normal((hkv, n_anchor, d), dtype=np.float32)
+    frames, queries, qpos = [], [], []
+    for step in range(1, n_steps + 1):
+        Q = rng.standard_normal((hq, n, d), dtype=np.float32)
+        w = query_direction(u, step)
+        for h in range(hq):
+            Q[h] += np.float32(np.sqrt(d)) * w[h // rep][None, :]
+        queries.append(rnd(Q))
+        qpos.append(grid_positions(step, gh, gw, n_text))
+        Kf = rng.standard_normal((hkv, n, d), dtype=np.float32) + np.float32(0.3) * u[:, step][:, None, :]
+        Vf = rng.standard_normal((hkv, n, d), dtype=np.float32)
+        frames.append((rnd(Kf), rnd(Vf), grid_positions(step, gh, gw, n_text)))
+    return RollingCase(dtype, hq, hkv, d, n_text, gh, gw, tuple(sections), 10000.0, rnd(aK), rnd(aV),
+                       cache_positions(n_text, gh, gw, 0), segment_table(n_text, n, 0), frames, queries, qpos,
+                       strided_rows(n, n_score))

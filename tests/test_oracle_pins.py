@@ -391,3 +391,89 @@ def test_bf16_rounding_helpers():
     assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8)
     bits = synth.bf16_bits(synth.to_bf16(x.astype(np.float32)))
     np.testing.assert_array_equal(orc.bf16_bits_to_f64(bits), r)
+
+
+# ------------------------------------------------------------------- rolling rollout pins
+def _tiny_rolling(seed=5, n_steps=4, n=5, d=8, n_anchor=3, hq=2, hkv=1):
+    rng = np.random.default_rng(seed)
+    aK, aV = rng.standard_normal((hkv, n_anchor, d)), rng.standard_normal((hkv, n_anchor, d))
+    apos = np.stack([np.arange(n_anchor)] * 3, axis=1)
+    frames = [(rng.standard_normal((hkv, n, d)), rng.standard_normal((hkv, n, d)),
+               np.stack([np.full(n, 10 + j), np.arange(n), np.arange(n)], axis=1)) for j in range(1, n_steps + 1)]
+    queries = [rng.standard_normal((hq, n, d)) for _ in range(n_steps)]
+    return aK, aV, apos, [(0, n_anchor, orc.SEG_TEXT, -1)], frames, queries
+
+
+def test_rolling_rollout_with_full_budgets_is_dense_attention_at_every_step():
+    aK, aV, apos, asegs, frames, queries = _tiny_rolling()
+    steps = orc.rolling_rollout(aK, aV, apos, asegs, frames, queries, 0.3, lambda w: [5] * w)
+    for i, st in enumerate(steps):
+        K = np.concatenate([aK] + [f[0] for f in frames[:i]], axis=1)
+        V = np.concatenate([aV] + [f[1] for f in frames[:i]], axis=1)
+        O, L = orc.frame_attn(queries[i], K, V, 0.3)
+        np.testing.assert_allclose(st["O"], O, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(st["lse"], L, rtol=0, atol=1e-13)
+        assert np.array_equal(st["K"], K) and st["segments"][-1][1] == (5 if i else 3)
+
+
+def test_rolling_rollout_matches_step_by_step_brute_force():
+    # independent restatement with Python loops: explicit cache lists, brute-force scores,
+    # selection by sorting (score descending, position ascending)
+    aK, aV, apos, asegs, frames, queries = _tiny_rolling(seed=9)
+    budget = lambda w: orc.budget_pow(5, w, 0.6, 1)          # 3, 1, 1, ...
+    steps = orc.rolling_rollout(aK, aV, apos, asegs, frames, queries, 0.3, budget)
+    cache = [("a", i) for i in range(3)]                      # (frame id, token) of every cached row
+    rowK = {("a", i): aK[0, i] for i in range(3)}
+    for step, Q in enumerate(queries):
+        if step >= 1:
+            for t in range(5):
+                cache.append((step, t))
+                rowK[(step, t)] = frames[step - 1][0][0, t]
+        Kc = np.stack([rowK[c] for c in cache])[None]
+        sc = orc.score_bruteforce(Q, Kc, 0.3)[0]
+        b = budget(step)
+        keep = [c for c in cache if c[0] == "a"]
+        for j in range(1, step + 1):
+            rows = [(sc[r], r) for r, c in enumerate(cache) if c[0] == j]
+            rows.sort(key=lambda x: (-x[0], x[1]))
+            chosen = sorted(r for _, r in rows[:b[step - j]])     # distance of frame j is step + 1 - j
+            keep += [cache[r] for r in chosen]
+        cache = keep
+        got = [("a", int(p[1])) if p[0] < 10 else (int(p[0]) - 10, int(p[1])) for p in steps[step]["pos"][0]]
+        assert got == cache, f"step {step + 1}"
+
+
+def test_rolling_rollout_survivors_are_nested_and_counts_follow_the_budgets():
+    case = synth.rolling_case(seed=2, n_steps=5, hq=2, hkv=1, gh=4, gw=6, n_text=5, n_score=12, dtype="f32")
+    n = case.n_frame
+    steps = orc.rolling_rollout(case.anchor_K, case.anchor_V, case.anchor_pos, case.anchor_segments, case.frames,
+                                case.queries, case.scale, lambda w: orc.budget_pow(n, w, 0.7, 3),
+                                score_rows=case.score_rows)
+    prev = None
+    for i, st in enumerate(steps):
+        b = orc.budget_pow(n, i, 0.7, 3)
+        lens = [s[1] for s in st["segments"] if s[2] == orc.SEG_FRAME]
+        assert lens == [b[i - 1 - j] for j in range(i)]          # oldest first; newest at distance 1
+        rows = {tuple(r) for r in st["pos"][0]}
+        if prev is not None:
+            newest = {tuple(r) for r in case.frames[i - 1][2]}
+            assert rows <= prev | newest                          # nothing evicted ever comes back
+        prev = rows
+    # the first compaction of a frame starts from the whole frame: rolling == one-shot there
+    Kd = np.concatenate([case.anchor_K, case.frames[0][0]], axis=1)
+    Vd = np.concatenate([case.anchor_V, case.frames[0][1]], axis=1)
+    pd = np.concatenate([case.anchor_pos, case.frames[0][2]], axis=0)[None]
+    segs = case.anchor_segments + [(case.anchor_K.shape[1], n, orc.SEG_FRAME, 1)]
+    sc = orc.score(case.queries[1][:, case.score_rows], Kd, case.scale)
+    Kp, Vp, pp, _, _ = orc.compact(Kd, Vd, pd, sc, segs, [s[1] for s in case.anchor_segments] + [orc.budget_pow(n, 1, 0.7, 3)[0]])
+    assert np.array_equal(steps[1]["K"], Kp) and np.array_equal(steps[1]["pos"], pp)
+
+
+def test_rolling_rollout_sliding_window_keeps_only_the_newest_frame():
+    aK, aV, apos, asegs, frames, queries = _tiny_rolling(seed=1)
+    steps = orc.rolling_rollout(aK, aV, apos, asegs, frames, queries, 0.3, lambda w: orc.budget_slide(5, w))
+    for i, st in enumerate(steps[1:], start=1):
+        assert [s[1] for s in st["segments"] if s[2] == orc.SEG_FRAME] == [0] * (i - 1) + [5]
+        K = np.concatenate([aK, frames[i - 1][0]], axis=1)
+        V = np.concatenate([aV, frames[i - 1][1]], axis=1)
+        np.testing.assert_allclose(st["O"], orc.frame_attn(queries[i], K, V, 0.3)[0], rtol=0, atol=1e-13)
