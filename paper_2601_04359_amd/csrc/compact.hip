@@ -125,8 +125,12 @@ __global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ sc
 // of the segment, kItems keys per lane in registers.  The k-th largest key is found eight
 // bits at a time: keys that still match the prefix vote into a 256-bin LDS histogram, the
 // 256 threads take a suffix sum over the bins (wave scan + one exchange) and the bin that
-// contains the k-th key extends the prefix.  The ordered output needs one more exchange
-// (keys above the threshold and keys equal to it, per wave).
+// contains the k-th key extends the prefix; as soon as that bin holds a single key, the
+// key itself is the threshold and the remaining passes are skipped.  Scores of one segment
+// crowd into a few bins on the leading bits, so the histogram is kept in 32 copies laid out
+// [bin][lane % 32]: a vote lands in the voter's own LDS bank and votes of one instruction
+// never queue behind each other.  The ordered output needs one more exchange (keys above
+// the threshold and keys equal to it, per wave).
 // Blocks also clear the in-place gather's ticket counters and flags (n_clear words).
 template <int kItems>
 __global__ __launch_bounds__(256) void select_block_kernel(const float* __restrict__ score,
@@ -134,9 +138,10 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
                                                            int32_t* __restrict__ idx, int64_t idx_stride_h,
                                                            SegTable tab, int32_t* __restrict__ clear,
                                                            int n_clear) {
-  __shared__ int s_hist[256];
+  constexpr int kCopies = 32;
+  __shared__ __align__(16) int s_hist[256 * kCopies];
   __shared__ int s_wave_sum[4];
-  __shared__ int s_pick[2];  // chosen digit, keys above it
+  __shared__ int s_pick[4];  // chosen digit, keys above it, keys in it, the key when it is alone
   __shared__ int s_gt[4], s_eq[4];
   const int s = blockIdx.x, h = blockIdx.y;
   {
@@ -190,18 +195,25 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
   int remaining = k;
   while (hi > 0) {
     const int width = min(8, hi), shift = hi - width;
-    s_hist[threadIdx.x] = 0;
+    {
+      int4* h4 = reinterpret_cast<int4*>(s_hist);
+#pragma unroll
+      for (int i = 0; i < 256 * kCopies / 4 / 256; ++i) h4[i * 256 + threadIdx.x] = make_int4(0, 0, 0, 0);
+    }
     __syncthreads();
     const uint32_t hi_mask = hi >= 32 ? 0u : 0xFFFFFFFFu << hi;
     const uint32_t digit_mask = (1u << width) - 1u;
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
       const int e = base + i * 64 + lane;
-      if (e < len && (key[i] & hi_mask) == (prefix & hi_mask)) atomicAdd(&s_hist[(key[i] >> shift) & digit_mask], 1);
+      if (e < len && (key[i] & hi_mask) == (prefix & hi_mask))
+        atomicAdd(&s_hist[((key[i] >> shift) & digit_mask) * kCopies + (lane & (kCopies - 1))], 1);
     }
     __syncthreads();
+    int mine = 0;  // votes for bin threadIdx.x; the rotation keeps the reads of a wave on distinct banks
+#pragma unroll
+    for (int j = 0; j < kCopies; ++j) mine += s_hist[threadIdx.x * kCopies + ((j + threadIdx.x) & (kCopies - 1))];
     // suffix sums: above = number of matching keys with a digit larger than this thread's
-    const int mine = s_hist[threadIdx.x];
     int incl = mine;  // inclusive suffix sum inside the wave (towards higher lanes)
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -215,11 +227,21 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
     if (above < remaining && remaining <= above + mine) {  // exactly one thread
       s_pick[0] = threadIdx.x;
       s_pick[1] = above;
+      s_pick[2] = mine;
     }
     __syncthreads();
     prefix |= static_cast<uint32_t>(s_pick[0]) << shift;
     remaining -= s_pick[1];
     hi = shift;
+    if (s_pick[2] == 1 && hi > 0) {  // block-uniform: the bin's only key is the k-th largest
+      const uint32_t lo_mask = 0xFFFFFFFFu << hi;
+#pragma unroll
+      for (int i = 0; i < kItems; ++i)
+        if (base + i * 64 + lane < len && (key[i] & lo_mask) == prefix) s_pick[3] = static_cast<int>(key[i]);
+      __syncthreads();
+      prefix = static_cast<uint32_t>(s_pick[3]);
+      hi = 0;  // remaining is 1 here: the key itself is taken
+    }
   }
   int gt = 0, eq = 0;
 #pragma unroll

@@ -1,0 +1,90 @@
+"""Rolling PackCache for one attention layer: the cache stays packed across frame steps.
+
+Host-side bookkeeping only (buffers, the segment table, which C-ABI call comes next); every
+step of the path runs in libpackcache kernels.  Per frame step (Sec. 3.4, Fig. 5(b)):
+
+    reserve()/commit()  the frame generated last is appended whole (keys rotated on insert)
+    pc_score            importance of every cached key under the step's queries
+    pc_budget           per-distance token budgets (config rule or the paper's Eq. 6 / Eq. 7)
+    pc_compact          in place: anchors stay, each past frame keeps its top-budget keys
+    pc_frame_attn       the step's queries over the packed cache
+
+Eviction is irreversible: a frame's candidates at one step are its survivors of the step
+before.  With mode "dense" nothing is evicted (the full-cache baseline); with mode "slide"
+only the newest frame survives (the sliding-window baseline of Sec. 3.3).
+"""
+from __future__ import annotations
+
+from . import binding as pk
+
+MODES = {"pow": pk.PC_BUDGET_POW, "norm": pk.PC_BUDGET_NORM, "half": pk.PC_BUDGET_HALF,
+         "slide": pk.PC_BUDGET_SLIDE, "dense": None}
+
+
+class RollingLayer:
+    """The packed K/V cache of one layer in HBM and its host-side segment table."""
+
+    def __init__(self, Hq: int, Hkv: int, D: int, capacity: int, n_frame: int, scale: float,
+                 mode: str = "pow", gamma: float = 0.85, b_min: int = 512, budget_tokens: int | None = None,
+                 n_score: int = 512, sections=(32, 48, 48), base: float = 10000.0, dtype=None, device="cuda:0"):
+        import torch
+        if mode not in MODES:
+            raise ValueError(f"mode {mode!r} not in {sorted(MODES)}")
+        self.Hq, self.Hkv, self.D, self.capacity, self.n_frame = Hq, Hkv, D, capacity, n_frame
+        self.scale, self.mode, self.gamma, self.b_min = scale, mode, gamma, b_min
+        # POW floors gamma^d of a whole frame; NORM / HALF / SLIDE split a fixed token budget
+        self.budget_tokens = n_frame if budget_tokens is None else budget_tokens
+        self.sections, self.base = tuple(sections), base
+        dtype = torch.bfloat16 if dtype is None else dtype
+        self.K = torch.empty((Hkv, capacity, D), dtype=dtype, device=device)
+        self.V = torch.empty_like(self.K)
+        self.pos = torch.empty((Hkv, capacity, 3), dtype=torch.int32, device=device)
+        self.score = torch.empty((Hkv, capacity), dtype=torch.float32, device=device)
+        self.segments: list[tuple[int, int, int, int]] = []
+        self.nk = 0
+        n_rows = min(n_score, n_frame)
+        self.q_rows = ((torch.arange(n_rows, dtype=torch.int64) * n_frame) // n_rows).to(torch.int32).to(device)
+        self._ws_score = torch.empty(pk.pc_score_workspace_bytes(Hq, Hkv, n_rows, capacity), dtype=torch.uint8,
+                                     device=device)
+        self._ws_compact = torch.empty(pk.pc_compact_workspace_bytes(Hkv, capacity), dtype=torch.uint8,
+                                       device=device)
+
+    # ---- insertion: the producer writes straight into the cache, no copy ----------------------
+    def reserve(self, n: int):
+        """Views of the next n free rows: (K rows, V rows, pos rows [Hkv][n][3])."""
+        if self.nk + n > self.capacity:
+            raise ValueError(f"cache capacity {self.capacity} < {self.nk} + {n}")
+        a = self.nk
+        return self.K[:, a:a + n], self.V[:, a:a + n], self.pos[:, a:a + n]
+
+    def commit(self, n: int, kind: int, frame: int, rotate_with=None) -> None:
+        """Make the n reserved rows part of the cache.  rotate_with: int32 [n][3] device
+        positions; when given the new keys are rotated in place (a1) on insertion."""
+        a = self.nk
+        if rotate_with is not None:
+            pk.pc_rope3d(self.K[:, a:a + n], rotate_with, self.sections, self.base)
+        self.segments.append((a, n, kind, frame))
+        self.nk = a + n
+
+    # ---- one frame step -----------------------------------------------------------------------
+    def budgets(self) -> list[int]:
+        """Budget of every segment for the cache as it stands (anchors: their length)."""
+        n_past = sum(1 for s in self.segments if s[2] == pk.PC_SEG_FRAME)
+        if self.mode == "dense":
+            return [s[1] for s in self.segments]
+        if self.mode == "pow":
+            per_d = pk.pc_budget(pk.PC_BUDGET_POW, self.n_frame, n_past, self.gamma, self.b_min)
+        else:
+            per_d = pk.pc_budget(MODES[self.mode], self.budget_tokens, n_past, self.gamma, self.b_min)
+        return pk.segment_budgets(self.segments, per_d)
+
+    def step(self, Q, O=None, q_pos=None, lse=None):
+        """Queries Q [Hq][n_frame][D] of the frame being generated -> O.  q_pos (int32
+        [n_frame][3], device): rotate Q in place first."""
+        if q_pos is not None:
+            pk.pc_rope3d(Q, q_pos, self.sections, self.base)
+        if self.mode != "dense":
+            pk.pc_score(Q, self.K, self.nk, self.scale, score=self.score, ws=self._ws_score, q_rows=self.q_rows)
+            self.segments, self.nk = pk.pc_compact(self.K, self.V, self.pos, self.score, self.segments,
+                                                   self.budgets(), ws=self._ws_compact)
+        return pk.pc_frame_attn(Q, self.K, self.V, self.nk, self.scale, O=O, lse=lse)
