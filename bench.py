@@ -46,6 +46,12 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--sweep", action="store_true", help="per-frame dense vs packed, frames 1..48")
+    ap.add_argument("--rollout", action="store_true",
+                    help="48-frame rollout of a 28-layer stack (24 query / 8 KV heads), rolling packed cache "
+                         "vs dense cache; per-frame curve written to gpurun_out/rollout.json")
+    ap.add_argument("--rollout-layers", type=int, default=28)
+    ap.add_argument("--rollout-frames", type=int, default=48)
+    ap.add_argument("--rollout-mode", default="pow", help="pow | norm | half | slide")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-f48", action="store_true", help="skip the frame-48 compaction / dense legs")
     ap.add_argument("--no-dense", action="store_true",
@@ -262,6 +268,80 @@ def main() -> int:
             with open(os.path.join(ROOT, "gpurun_out", "sweep.json"), "w") as fh:
                 json.dump(table, fh, indent=0)
         del K48, V48, Q48, Kw, Vw
+
+    # ------------------------------------------------------------------ 48-frame rollout of a layer stack
+    if args.rollout:
+        from paper_2601_04359_amd.rollout import RollingLayer
+        L, F = args.rollout_layers, args.rollout_frames
+        hq5, hkv5, n_text, gh, gw = 24, 8, 256, 48, 84
+        n = gh * gw
+        n_anchor = n_text + n
+        sections, scale5 = (32, 48, 48), 1.0 / float(np.sqrt(D))
+        tok_budget = n            # NORM / HALF / SLIDE: one frame's worth of tokens over all past frames
+        cap_packed = n_anchor + n + (sum(pk.pc_budget(pk.PC_BUDGET_POW, n, F - 1, 0.85, 512))
+                                     if args.rollout_mode == "pow" else tok_budget + n)
+        cap_dense = n_anchor + (F - 1) * n
+        streams = [synth.DeviceRollingStream(1000 * (l + 1), hq5, hkv5, D, F, sections, dev) for l in range(L)]
+        packed = [RollingLayer(hq5, hkv5, D, cap_packed, n, scale5, mode=args.rollout_mode, gamma=0.85, b_min=512,
+                               budget_tokens=tok_budget, n_score=512, sections=sections, device=dev)
+                  for _ in range(L)]
+        dense = [RollingLayer(hq5, hkv5, D, cap_dense, n, scale5, mode="dense", sections=sections, device=dev)
+                 for _ in range(L)]
+        apos = up(synth.cache_positions(n_text, gh, gw, 0), bf=False)
+        for l in range(L):               # prefill: anchors, rotated on insert
+            for lay in (packed[l], dense[l]):
+                k, v, p = lay.reserve(n_anchor)
+                if lay is packed[l]:
+                    streams[l].anchors(k, v)
+                else:
+                    k.copy_(packed[l].K[:, :n_anchor]); v.copy_(packed[l].V[:, :n_anchor])
+                p.copy_(apos[None].expand(hkv5, n_anchor, 3))
+            for lay, rot in ((dense[l], apos), (packed[l], apos)):
+                lay.commit(n_text, pk.PC_SEG_TEXT, -1, rotate_with=rot[:n_text])
+                lay.commit(n, pk.PC_SEG_COND, 0, rotate_with=rot[n_text:])
+        Qp = [torch.empty((hq5, n, D), dtype=torch.bfloat16, device=dev) for _ in range(L)]
+        Qd = [torch.empty_like(q) for q in Qp]
+        O5 = torch.empty_like(Qp[0])
+        curve = []
+        for f in range(1, F + 1):
+            fpos = up(synth.grid_positions(f, gh, gw, n_text), bf=False)
+            ppos = up(synth.grid_positions(f - 1, gh, gw, n_text), bf=False) if f >= 2 else None
+            for l in range(L):           # untimed: draw this step's inputs into the caches / query buffers
+                streams[l].queries(f, Qp[l])
+                Qd[l].copy_(Qp[l])
+                if f >= 2:
+                    k, v, p = packed[l].reserve(n)
+                    streams[l].frame(f - 1, k, v)
+                    p.copy_(ppos[None].expand(hkv5, n, 3))
+                    kd, vd, pd = dense[l].reserve(n)
+                    kd.copy_(k); vd.copy_(v); pd.copy_(p)
+            torch.cuda.synchronize()
+            times = {}
+            for name, layers, Qs in (("packed", packed, Qp), ("dense", dense, Qd)):
+                a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for l in range(L):
+                    if f >= 2:
+                        layers[l].commit(n, pk.PC_SEG_FRAME, f - 1, rotate_with=ppos)
+                    layers[l].step(Qs[l], O=O5, q_pos=fpos)
+                e.record()
+                torch.cuda.synchronize()
+                times[name] = a.elapsed_time(e)
+            curve.append({"frame": f, "Nk_dense": dense[0].nk, "Nk_packed": packed[0].nk,
+                          "dense_ms": round(times["dense"], 3), "packed_ms": round(times["packed"], 3)})
+        tp, td = sum(r["packed_ms"] for r in curve), sum(r["dense_ms"] for r in curve)
+        last4 = curve[-4:]
+        out["rollout"] = {"layers": L, "frames": F, "Hq": hq5, "Hkv": hkv5, "mode": args.rollout_mode,
+                          "packed_total_s": round(tp / 1e3, 4), "dense_total_s": round(td / 1e3, 4),
+                          "speedup_total": round(td / tp, 3),
+                          "speedup_last4": round(sum(r["dense_ms"] for r in last4) / sum(r["packed_ms"] for r in last4), 3),
+                          "last_frame": curve[-1],
+                          "note": "packed_ms covers rope, score, budget, in-place compaction and attention of all "
+                                  "layers; dense_ms rope and attention over the full cache"}
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "rollout.json"), "w") as fh:
+            json.dump(curve, fh, indent=0)
+        del packed, dense, Qp, Qd, streams
 
     # ------------------------------------------------------------------ CPU baseline: the oracle
     if not args.no_cpu:

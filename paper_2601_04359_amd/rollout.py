@@ -39,15 +39,16 @@ class RollingLayer:
         self.K = torch.empty((Hkv, capacity, D), dtype=dtype, device=device)
         self.V = torch.empty_like(self.K)
         self.pos = torch.empty((Hkv, capacity, 3), dtype=torch.int32, device=device)
-        self.score = torch.empty((Hkv, capacity), dtype=torch.float32, device=device)
         self.segments: list[tuple[int, int, int, int]] = []
         self.nk = 0
         n_rows = min(n_score, n_frame)
         self.q_rows = ((torch.arange(n_rows, dtype=torch.int64) * n_frame) // n_rows).to(torch.int32).to(device)
-        self._ws_score = torch.empty(pk.pc_score_workspace_bytes(Hq, Hkv, n_rows, capacity), dtype=torch.uint8,
-                                     device=device)
-        self._ws_compact = torch.empty(pk.pc_compact_workspace_bytes(Hkv, capacity), dtype=torch.uint8,
-                                       device=device)
+        if mode != "dense":   # the full-cache baseline neither scores nor compacts
+            self.score = torch.empty((Hkv, capacity), dtype=torch.float32, device=device)
+            self._ws_score = torch.empty(pk.pc_score_workspace_bytes(Hq, Hkv, n_rows, capacity), dtype=torch.uint8,
+                                         device=device)
+            self._ws_compact = torch.empty(pk.pc_compact_workspace_bytes(Hkv, capacity), dtype=torch.uint8,
+                                           device=device)
 
     # ---- insertion: the producer writes straight into the cache, no copy ----------------------
     def reserve(self, n: int):

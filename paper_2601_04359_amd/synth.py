@@ -270,3 +270,38 @@ def rolling_case(seed: int = 11, n_steps: int = 6, hq: int = 8, hkv: int = 2, d:
     return RollingCase(dtype, hq, hkv, d, n_text, gh, gw, tuple(sections), 10000.0, rnd(aK), rnd(aV),
                        cache_positions(n_text, gh, gw, 0), segment_table(n_text, n, 0), frames, queries, qpos,
                        strided_rows(n, n_score))
+
+
+class DeviceRollingStream:
+    """The rolling_case recipe drawn on the GPU (torch generator, seeded per layer) for
+    rollouts too large to draw on the host: fills caller-provided bf16 buffers in place."""
+
+    def __init__(self, seed: int, hq: int, hkv: int, d: int, n_frames: int, sections=(32, 48, 48),
+                 device: str = "cuda:0"):
+        import torch
+        self.torch = torch
+        self.hq, self.hkv, self.d = hq, hkv, d
+        u = rolling_directions(np.random.default_rng(seed), hkv, d, n_frames + 1, sections)
+        self.u = torch.from_numpy(u).to(device)                                  # [Hkv][n_frames+1][D]
+        self.w = [torch.from_numpy(query_direction(u, step)).to(device) for step in range(1, n_frames + 1)]
+        self.gen = torch.Generator(device=device)
+        self.gen.manual_seed(seed)
+
+    def _fill(self, out, shift):
+        out.normal_(generator=self.gen)
+        if shift is not None:
+            out.add_(shift[:, None, :].to(out.dtype))
+
+    def anchors(self, out_k, out_v):
+        self._fill(out_k, 0.5 * self.u[:, 0])
+        self._fill(out_v, None)
+
+    def frame(self, j: int, out_k, out_v):
+        """Keys / values of generated frame j (1-based)."""
+        self._fill(out_k, 0.3 * self.u[:, j])
+        self._fill(out_v, None)
+
+    def queries(self, step: int, out_q):
+        """Queries of the step that generates frame `step` (1-based)."""
+        rep = self.hq // self.hkv
+        self._fill(out_q, float(np.sqrt(self.d)) * self.w[step - 1].repeat_interleave(rep, dim=0))
