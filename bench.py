@@ -52,6 +52,9 @@ def main() -> int:
     ap.add_argument("--rollout-layers", type=int, default=28)
     ap.add_argument("--rollout-frames", type=int, default=48)
     ap.add_argument("--rollout-mode", default="pow", help="pow | norm | half | slide")
+    ap.add_argument("--rollout-passes", type=int, default=1,
+                    help="attention passes per frame and layer (iterative decoding): with more than one, the "
+                         "first pass runs on the un-packed cache and its log-sum-exp feeds the scoring")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-f48", action="store_true", help="skip the frame-48 compaction / dense legs")
     ap.add_argument("--no-dense", action="store_true",
@@ -302,6 +305,7 @@ def main() -> int:
         Qp = [torch.empty((hq5, n, D), dtype=torch.bfloat16, device=dev) for _ in range(L)]
         Qd = [torch.empty_like(q) for q in Qp]
         O5 = torch.empty_like(Qp[0])
+        lse5 = torch.empty((hq5, n), dtype=torch.float32, device=dev)
         curve = []
         for f in range(1, F + 1):
             fpos = up(synth.grid_positions(f, gh, gw, n_text), bf=False)
@@ -323,7 +327,14 @@ def main() -> int:
                 for l in range(L):
                     if f >= 2:
                         layers[l].commit(n, pk.PC_SEG_FRAME, f - 1, rotate_with=ppos)
-                    layers[l].step(Qs[l], O=O5, q_pos=fpos)
+                    if args.rollout_passes == 1:
+                        layers[l].step(Qs[l], O=O5, q_pos=fpos)
+                    else:
+                        pk.pc_rope3d(Qs[l], fpos, sections, 10000.0)
+                        layers[l].attend(Qs[l], O=O5, lse=lse5)
+                        layers[l].refresh(Qs[l], lse=lse5)
+                        for _ in range(args.rollout_passes - 1):
+                            layers[l].attend(Qs[l], O=O5)
                 e.record()
                 torch.cuda.synchronize()
                 times[name] = a.elapsed_time(e)
@@ -332,6 +343,7 @@ def main() -> int:
         tp, td = sum(r["packed_ms"] for r in curve), sum(r["dense_ms"] for r in curve)
         last4 = curve[-4:]
         out["rollout"] = {"layers": L, "frames": F, "Hq": hq5, "Hkv": hkv5, "mode": args.rollout_mode,
+                          "passes_per_frame": args.rollout_passes,
                           "packed_total_s": round(tp / 1e3, 4), "dense_total_s": round(td / 1e3, 4),
                           "speedup_total": round(td / tp, 3),
                           "speedup_last4": round(sum(r["dense_ms"] for r in last4) / sum(r["packed_ms"] for r in last4), 3),

@@ -115,8 +115,12 @@ int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride_h,
  *   q_rows dev or NULL, int32 [n_qs]: rows of Qs that score (the same for every head),
  *          e.g. an evenly spread sample of the frame.  NULL: rows 0 .. n_qs-1.
  *   K      dev, [Hkv][Nk][D]   cached keys (already rotated), head stride k_stride_h
- *   lse    dev or NULL, fp32 [Hq][n_qs]: natural-log sum-exp of each scoring query's scaled logits
- *          over the same Nk keys.  NULL: computed here (one extra QK^T pass).
+ *   lse    dev or NULL, fp32, head stride lse_stride_h, indexed like the rows of Qs (row
+ *          q_rows[i] of head h is lse[h * lse_stride_h + q_rows[i]]; without q_rows, row i):
+ *          natural-log sum-exp of that query's scaled logits over the same Nk keys, e.g.
+ *          the lse output of a pc_frame_attn call over the same cache (Sec. 3.4: the mask
+ *          is refreshed from attention the model computes anyway).  NULL: computed here
+ *          (one extra QK^T pass).
  *   score  dev, fp32 [Hsel][Nk], head stride score_stride_h; Hsel = Hkv, or 1 when
  *          share_heads != 0 (mass summed over the KV heads as well).
  * Summation order is fixed (no atomics): results are bit-reproducible.
@@ -126,8 +130,8 @@ int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride_h,
 size_t pc_score_workspace_bytes(int Hq, int Hkv, int n_qs, int Nk, int share_heads);
 int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hkv, int n_qs, int Nk,
              int D, int64_t q_stride_h, int64_t k_stride_h, const int32_t* q_rows, float scale,
-             const float* lse, float* score, int64_t score_stride_h, int share_heads, void* ws,
-             size_t ws_bytes, void* stream);
+             const float* lse, int64_t lse_stride_h, float* score, int64_t score_stride_h,
+             int share_heads, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * pc_compact_plan -- host half of compaction: the segment table and key count after

@@ -62,7 +62,7 @@ def lib() -> C.CDLL:
         L.pc_score_workspace_bytes.restype = sz
         L.pc_score_workspace_bytes.argtypes = [C.c_int] * 5
         L.pc_score.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i64, i64, vp,
-                               C.c_float, vp, vp, i64, C.c_int, vp, sz, vp]
+                               C.c_float, vp, i64, vp, i64, C.c_int, vp, sz, vp]
         L.pc_compact_plan.argtypes = [segp, C.c_int, i32p, segp, i32p]
         L.pc_compact_workspace_bytes.restype = sz
         L.pc_compact_workspace_bytes.argtypes = [C.c_int] * 3
@@ -155,7 +155,8 @@ def pc_score_workspace_bytes(Hq: int, Hkv: int, n_qs: int, Nk: int, share_heads:
 def pc_score(Qs, K, Nk: int, scale: float, lse=None, score=None, share_heads: bool = False, ws=None,
              q_rows=None):
     """Qs [Hq][rows][D], K [Hkv][>=Nk][D] -> score fp32 [Hsel][Nk].  q_rows (int32, device)
-    picks the rows of Qs that score; None: all of them."""
+    picks the rows of Qs that score; None: all of them.  lse (fp32 [Hq][rows], optional) is
+    indexed like the rows of Qs."""
     import torch
     Hq, n_qs, D = Qs.shape
     if q_rows is not None:
@@ -169,7 +170,8 @@ def pc_score(Qs, K, Nk: int, scale: float, lse=None, score=None, share_heads: bo
     if ws is None:
         ws = _workspace(pc_score_workspace_bytes(Hq, Hkv, n_qs, Nk, share_heads), K)
     _check(lib().pc_score(Qs.data_ptr(), K.data_ptr(), _dtype_code(K), Hq, Hkv, n_qs, Nk, D, Qs.stride(0),
-                          K.stride(0), _ptr(q_rows), float(scale), _ptr(lse), score.data_ptr(), score.stride(0),
+                          K.stride(0), _ptr(q_rows), float(scale), _ptr(lse), 0 if lse is None else lse.stride(0),
+                          score.data_ptr(), score.stride(0),
                           int(share_heads), ws.data_ptr(), ws.numel(), _stream()))
     return score
 

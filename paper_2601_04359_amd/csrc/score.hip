@@ -230,13 +230,15 @@ __global__ void score_merge_rows(const float2* __restrict__ part, float* __restr
   lse2[r] = m + log2f(l);
 }
 
-// A caller's natural-log LSE [head][n_qs] -> the padded base-2 layout of pass 2.
-__global__ void score_import_lse(const float* __restrict__ lse, float* __restrict__ lse2, int Hq, int n_qs,
-                                 int n_pad) {
+// A caller's natural-log LSE, indexed like the rows of Qs, -> the dense [head][n_pad] layout
+// of pass 2 (times `mul`: log2(e) for the base-2 kernels); padding rows get +inf.
+__global__ void score_import_lse(const float* __restrict__ lse, int64_t lse_stride_h,
+                                 const int32_t* __restrict__ q_rows, float* __restrict__ out, int Hq, int n_qs,
+                                 int n_pad, float mul) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= Hq * n_pad) return;
   const int h = r / n_pad, row = r % n_pad;
-  lse2[r] = row < n_qs ? lse[static_cast<int64_t>(h) * n_qs + row] * 1.4426950408889634f : INFINITY;
+  out[r] = row < n_qs ? lse[h * lse_stride_h + (q_rows ? q_rows[row] : row)] * mul : INFINITY;
 }
 
 // ---- pass 2: column mass --------------------------------------------------------------------
@@ -530,7 +532,8 @@ extern "C" size_t pc_score_workspace_bytes(int Hq, int Hkv, int n_qs, int Nk, in
 
 extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hkv, int n_qs,
                         int Nk, int D, int64_t q_stride_h, int64_t k_stride_h,
-                        const int32_t* q_rows, float scale, const float* lse, float* score, int64_t score_stride_h, int share_heads,
+                        const int32_t* q_rows, float scale, const float* lse, int64_t lse_stride_h, float* score,
+                        int64_t score_stride_h, int share_heads,
                         void* ws, size_t ws_bytes, void* stream) {
   PC_REQUIRE(dtype == PC_F32 || dtype == PC_BF16, PC_ERR_DTYPE, "pc_score: dtype %d", dtype);
   PC_REQUIRE(Hq > 0 && Hkv > 0 && Hq % Hkv == 0, PC_ERR_SHAPE,
@@ -543,6 +546,8 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
              PC_ERR_SHAPE, "pc_score: a head stride is smaller than rows*D");
   PC_REQUIRE(share_heads || Hkv == 1 || score_stride_h >= Nk, PC_ERR_SHAPE,
              "pc_score: score head stride %lld < Nk", static_cast<long long>(score_stride_h));
+  PC_REQUIRE(lse == nullptr || Hq == 1 || lse_stride_h >= n_qs, PC_ERR_SHAPE,
+             "pc_score: lse head stride %lld < n_qs", static_cast<long long>(lse_stride_h));
   const WsLayout lay = ws_layout(Hq, Hkv, n_qs, Nk, share_heads);
   PC_REQUIRE(ws != nullptr && ws_bytes >= lay.total, PC_ERR_WORKSPACE,
              "pc_score: workspace %zu bytes, need %zu", ws_bytes, lay.total);
@@ -577,7 +582,8 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
       score_merge_rows<<<ceil_div(Hq * n_pad, 256), 256, 0, s>>>(ws_part, ws_lse, Hq, n_qs, n_pad, n_splits);
       PC_CHECK_LAUNCH("pc_score merge");
     } else {
-      score_import_lse<<<ceil_div(Hq * n_pad, 256), 256, 0, s>>>(lse, ws_lse, Hq, n_qs, n_pad);
+      score_import_lse<<<ceil_div(Hq * n_pad, 256), 256, 0, s>>>(lse, lse_stride_h, q_rows, ws_lse, Hq, n_qs, n_pad,
+                                                                 1.4426950408889634f);
       PC_CHECK_LAUNCH("pc_score lse import");
     }
     const int n_key_blocks = ceil_div(Nk, kBlockRows);
@@ -600,15 +606,17 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
     const int64_t per_head_stride = share_heads ? Nk : score_stride_h;
     const float* q = static_cast<const float*>(Qs);
     const float* k = static_cast<const float*>(K);
-    const float* lse_in = lse;
-    if (lse == nullptr) {
+    const float* lse_in = ws_lse;
+    if (lse != nullptr) {
+      score_import_lse<<<ceil_div(Hq * n_qs, 256), 256, 0, s>>>(lse, lse_stride_h, q_rows, ws_lse, Hq, n_qs, n_qs, 1.f);
+      PC_CHECK_LAUNCH("pc_score lse import");
+    } else {
       const dim3 grid(ceil_div(n_qs, 64), Hq);
       if (D == 64)
         score_rowpass_f32<64><<<grid, 64, 0, s>>>(q, q_rows, k, ws_lse, rep, n_qs, Nk, q_stride_h, k_stride_h, scale);
       else
         score_rowpass_f32<128><<<grid, 64, 0, s>>>(q, q_rows, k, ws_lse, rep, n_qs, Nk, q_stride_h, k_stride_h, scale);
       PC_CHECK_LAUNCH("pc_score row pass");
-      lse_in = ws_lse;
     }
     const dim3 grid(ceil_div(Nk, 64), Hkv);
     if (D == 64)

@@ -9,6 +9,10 @@ step of the path runs in libpackcache kernels.  Per frame step (Sec. 3.4, Fig. 5
     pc_compact          in place: anchors stay, each past frame keeps its top-budget keys
     pc_frame_attn       the step's queries over the packed cache
 
+A model that makes several attention passes per frame (iterative decoding) calls attend()
+on the un-packed cache first, hands its log-sum-exp to refresh() and makes the remaining
+passes on the packed cache: the compaction is paid once per frame.
+
 Eviction is irreversible: a frame's candidates at one step are its survivors of the step
 before.  With mode "dense" nothing is evicted (the full-cache baseline); with mode "slide"
 only the newest frame survives (the sliding-window baseline of Sec. 3.3).
@@ -79,13 +83,25 @@ class RollingLayer:
             per_d = pk.pc_budget(MODES[self.mode], self.budget_tokens, n_past, self.gamma, self.b_min)
         return pk.segment_budgets(self.segments, per_d)
 
+    def refresh(self, Q, lse=None) -> None:
+        """Score every cached key under the (rotated) queries Q and re-pack the cache in
+        place.  lse (fp32 [Hq][n_frame]): log-sum-exp of Q's rows over the cache as it
+        stands, e.g. from attend(): scoring then needs one QK^T pass instead of two."""
+        if self.mode == "dense":
+            return
+        pk.pc_score(Q, self.K, self.nk, self.scale, lse=lse, score=self.score, ws=self._ws_score,
+                    q_rows=self.q_rows)
+        self.segments, self.nk = pk.pc_compact(self.K, self.V, self.pos, self.score, self.segments,
+                                               self.budgets(), ws=self._ws_compact)
+
+    def attend(self, Q, O=None, lse=None):
+        """The (rotated) queries Q over the cache as it stands -> O (and the log-sum-exp)."""
+        return pk.pc_frame_attn(Q, self.K, self.V, self.nk, self.scale, O=O, lse=lse)
+
     def step(self, Q, O=None, q_pos=None, lse=None):
         """Queries Q [Hq][n_frame][D] of the frame being generated -> O.  q_pos (int32
         [n_frame][3], device): rotate Q in place first."""
         if q_pos is not None:
             pk.pc_rope3d(Q, q_pos, self.sections, self.base)
-        if self.mode != "dense":
-            pk.pc_score(Q, self.K, self.nk, self.scale, score=self.score, ws=self._ws_score, q_rows=self.q_rows)
-            self.segments, self.nk = pk.pc_compact(self.K, self.V, self.pos, self.score, self.segments,
-                                                   self.budgets(), ws=self._ws_compact)
-        return pk.pc_frame_attn(Q, self.K, self.V, self.nk, self.scale, O=O, lse=lse)
+        self.refresh(Q)
+        return self.attend(Q, O=O, lse=lse)

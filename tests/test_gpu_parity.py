@@ -222,6 +222,22 @@ def test_score_with_supplied_lse_matches_internal_pass():
     assert got.shape == (w.Hkv, w.Nk)
 
 
+def test_score_reuses_the_lse_of_an_attention_pass_through_the_row_index():
+    # the LSE that pc_frame_attn emits for ALL query rows feeds pc_score for the sampled rows:
+    # one QK^T pass instead of two.  A row's probabilities scale by exp(-d_lse), so the score
+    # error is the attention kernel's LSE error (fp32 online softmax, ~1e-6) relative.
+    for w in (synth.midsize(), synth.config1()):
+        Q, K, V = dev(w.Q, w.dtype), dev(w.K, w.dtype), dev(w.V, w.dtype)
+        lse = torch.empty((w.Hq, w.Nq), dtype=torch.float32, device=DEV)
+        pk.pc_frame_attn(Q, K, V, w.Nk, w.scale, lse=lse)
+        rows = w.score_rows.astype(np.int32)
+        got = host(pk.pc_score(Q, K, w.Nk, w.scale, q_rows=dev(rows, None), lse=lse)).astype(np.float64)
+        want = orc.score(w.Q[:, rows], w.K, w.scale)
+        err = np.abs(got - want)
+        print("lse reuse", w.name, err.max(), (err / (want + 1e-30)).max())
+        assert np.all(err <= 2e-7 + 5e-5 * want), (err.max(), (err / (want + 1e-30)).max())
+
+
 def test_score_row_index_equals_gathered_rows():
     # scoring rows picked through q_rows must give the same bits as scoring a gathered copy
     for w in (synth.midsize(), synth.config1()):

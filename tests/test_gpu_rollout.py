@@ -91,3 +91,32 @@ def test_rotation_on_insert_equals_standalone_rotation():
     ref = dev(K, "bf16")
     pk.pc_rope3d(ref, pd, case.sections, case.base)
     assert torch.equal(layer.K[:, :n], ref) and layer.nk == n and layer.segments == [(0, n, pk.PC_SEG_FRAME, 1)]
+
+
+def test_attend_then_refresh_with_its_lse_keeps_the_same_rows():
+    # iterative decoding: first pass on the un-packed cache, its LSE feeds the scoring
+    case = synth.rolling_case(seed=11, n_steps=3)
+    aK, frames, queries = _rotated(case)
+    n = case.n_frame
+    mk = lambda: RollingLayer(case.Hq, case.Hkv, case.D, case.anchor_K.shape[1] + 3 * n, n, case.scale, mode="pow",
+                              gamma=0.85, b_min=32, n_score=case.score_rows.size, sections=case.sections,
+                              device=DEV)
+    a, b = mk(), mk()
+    for lay in (a, b):
+        for (start, length, kind, frame) in case.anchor_segments:
+            _insert(lay, aK[:, start:start + length], case.anchor_V[:, start:start + length],
+                    case.anchor_pos[start:start + length], kind, frame)
+    lse = torch.empty((case.Hq, n), dtype=torch.float32, device=DEV)
+    for i, Q in enumerate(queries):
+        if i >= 1:
+            for lay in (a, b):
+                _insert(lay, *frames[i - 1], pk.PC_SEG_FRAME, i)
+        Qd = dev(Q.astype(np.float32), "bf16")
+        Oa = a.step(Qd)
+        b.attend(Qd, lse=lse)
+        b.refresh(Qd, lse=lse)
+        Ob = b.attend(Qd)
+        assert a.segments == b.segments
+        # the two scorings differ by the LSE's fp32 rounding: same kept rows on this seed
+        assert torch.equal(a.pos[:, :a.nk], b.pos[:, :b.nk]) and torch.equal(a.K[:, :a.nk], b.K[:, :b.nk])
+        assert torch.equal(Oa, Ob)
