@@ -32,7 +32,7 @@ __all__ = [
     "SEG_TEXT", "SEG_COND", "SEG_FRAME", "SEG_SELF",
     "bf16_bits_to_f64", "round_to_bf16", "f64",
     "budget_pow", "budget_norm", "budget_half", "budget_slide",
-    "rope_angles", "rope3d",
+    "rope_angles", "rope3d", "rebase",
     "logits", "softmax_rows", "score", "select_topk", "compact", "packed_segments",
     "frame_attn", "frame_attn_bruteforce", "score_bruteforce", "rolling_rollout",
 ]
@@ -156,6 +156,19 @@ def rope3d(x: np.ndarray, pos: np.ndarray, sections: tuple[int, int, int], base:
     return out
 
 
+def rebase(K: np.ndarray, pos: np.ndarray, delta_t: int, sections: tuple[int, int, int], base: float):
+    """Temporal rebase of cached, already rotated keys (Sec. 3.4, the rebase equation):
+    pos_t <- pos_t - delta_t with pos_h, pos_w fixed.  Rotations about one axis compose, so a
+    key rotated at pos_t becomes the key rotated at pos_t - delta_t by one more rotation of
+    -delta_t on the temporal section only.  K [H][n][D], pos [..][n][3] -> (K', pos')."""
+    pos = np.asarray(pos)
+    shift = np.zeros((K.shape[1], 3), dtype=np.int64)
+    shift[:, 0] = -int(delta_t)
+    out_pos = pos.copy()
+    out_pos[..., 0] -= int(delta_t)
+    return rope3d(K, shift, sections, base), out_pos
+
+
 # --------------------------------------------------------------------------------------
 # attention pieces (Eq. 2).  For one frame's queries against earlier frames and the
 # anchors the causal mask is all-visible, so no mask appears.
@@ -263,34 +276,71 @@ def compact(K, V, pos, sc, segments, budgets, share_heads: bool = False):
 # its survivors of step f - 1)
 # --------------------------------------------------------------------------------------
 def rolling_rollout(anchor_K, anchor_V, anchor_pos, anchor_segments, frames, queries, scale: float,
-                    budget_fn, score_rows=None, share_heads: bool = False):
+                    budget_fn, score_rows=None, share_heads: bool = False, rotate=None, query_pos=None,
+                    rebase_t_scale=None, storage=None):
     """Generate-time cache management over several frame steps.
 
     anchor_K, anchor_V [Hkv][A][D], anchor_pos [A][3], anchor_segments: the always-kept
-    text / conditioning-image rows (keys already rotated).
-    frames[j] = (K_j, V_j, pos_j): keys (rotated), values and (t, h, w) of generated frame
-    j + 1, appended whole to the cache before the step that generates frame j + 2.
-    queries[i]: rotated queries [Hq][Nq][D] of step i + 1, which sees frames 1..i.
+    text / conditioning-image rows.
+    frames[j] = (K_j, V_j, pos_j): keys, values and (t, h, w) of generated frame j + 1,
+    appended whole to the cache before the step that generates frame j + 2.
+    queries[i]: queries [Hq][Nq][D] of step i + 1, which sees frames 1..i.
     budget_fn(n_past) -> per-distance budgets, entry d - 1 for distance d.
-    Each step: append the newest frame, score all cached keys with the scoring rows of the
-    step's queries, keep the per-frame top-budget keys (anchors whole), attend over what
-    is left.  Returns one dict per step: K, V, pos, segments (the packed cache the step
-    attended over), O and lse."""
+    rotate = None: keys and queries come already rotated.  rotate = (sections, base): they
+    come un-rotated and are rotated here, keys once on insertion, queries (at
+    query_pos[i]) at their step.
+    rebase_t_scale (needs rotate): sliding window.  The window advances when a step begins:
+    oldest frames that the previous step evicted completely leave the segment table and
+    every retained frame row is rebased by delta_t = rebase_t_scale * (frames dropped);
+    the frame appended now, the step's queries and everything that arrives later are
+    placed at their position minus the total shift so far, so scoring and attention of a
+    step see one consistent set of coordinates.  The anchors keep theirs.
+    storage: rounding applied to keys whenever they are written to the cache (the cache's
+    storage format), and to rotated queries; None keeps fp64.
+    Each step: slide the window, append the newest frame, score all cached keys with the
+    scoring rows of the step's queries, keep the per-frame top-budget keys (anchors whole),
+    attend over what is left.  Returns one dict per step: K, V, pos, segments (the cache
+    the step attended over), O, lse and the total temporal shift so far."""
+    store = (lambda a: a) if storage is None else storage
     hkv = np.asarray(anchor_K).shape[0]
     hsel = 1 if share_heads else hkv
-    K, V = f64(anchor_K), f64(anchor_V)
-    pos = np.broadcast_to(np.asarray(anchor_pos)[None], (hsel,) + np.asarray(anchor_pos).shape).copy()
+    anchor_pos = np.asarray(anchor_pos)
+    K = f64(anchor_K) if rotate is None else store(rope3d(anchor_K, anchor_pos, *rotate))
+    V = f64(anchor_V)
+    pos = np.broadcast_to(anchor_pos[None], (hsel,) + anchor_pos.shape).copy()
     segments = list(anchor_segments)
+    shift = 0
     steps = []
     for i, Q in enumerate(queries):
+        if rebase_t_scale is not None:
+            first = next((j for j, s in enumerate(segments) if s[2] == SEG_FRAME), len(segments))
+            n_drop = 0
+            while first + n_drop < len(segments) and segments[first + n_drop][1] == 0:
+                n_drop += 1
+            if n_drop and first + n_drop < len(segments):
+                delta = int(rebase_t_scale) * n_drop
+                segments = segments[:first] + segments[first + n_drop:]
+                a = segments[first][0]
+                Kr, pr = rebase(K[:, a:], pos[:, a:], delta, *rotate)
+                K = np.concatenate([K[:, :a], store(Kr)], axis=1)
+                pos = np.concatenate([pos[:, :a], pr], axis=1)
+                shift += delta
         if i >= 1:
             Kf, Vf, pf = frames[i - 1]
+            pf = np.asarray(pf).copy()
+            pf[:, 0] -= shift
+            Kf = f64(Kf) if rotate is None else store(rope3d(Kf, pf, *rotate))
             at = K.shape[1]
-            K = np.concatenate([K, f64(Kf)], axis=1)
+            K = np.concatenate([K, Kf], axis=1)
             V = np.concatenate([V, f64(Vf)], axis=1)
-            pos = np.concatenate([pos, np.broadcast_to(np.asarray(pf)[None], (hsel,) + np.asarray(pf).shape)], axis=1)
-            segments.append((at, np.asarray(Kf).shape[1], SEG_FRAME, i))
-        Q = f64(Q)
+            pos = np.concatenate([pos, np.broadcast_to(pf[None], (hsel,) + pf.shape)], axis=1)
+            segments.append((at, Kf.shape[1], SEG_FRAME, i))
+        if rotate is None:
+            Q = f64(Q)
+        else:
+            qp = np.asarray(query_pos[i]).copy()
+            qp[:, 0] -= shift
+            Q = store(rope3d(Q, qp, *rotate))
         n_past = sum(1 for s in segments if s[2] == SEG_FRAME)
         per_distance = budget_fn(n_past)
         # the newest past frame is the LAST frame segment: distance 1
@@ -304,7 +354,7 @@ def rolling_rollout(anchor_K, anchor_V, anchor_pos, anchor_segments, frames, que
         sc = score(Q if score_rows is None else Q[:, score_rows], K, scale, share_heads=share_heads)
         K, V, pos, _, segments = compact(K, V, pos, sc, segments, budgets, share_heads=share_heads)
         O, lse = frame_attn(Q, K, V, scale)
-        steps.append({"K": K, "V": V, "pos": pos, "segments": list(segments), "O": O, "lse": lse})
+        steps.append({"K": K, "V": V, "pos": pos, "segments": list(segments), "O": O, "lse": lse, "shift": shift})
     return steps
 
 

@@ -477,3 +477,54 @@ def test_rolling_rollout_sliding_window_keeps_only_the_newest_frame():
         K = np.concatenate([aK, frames[i - 1][0]], axis=1)
         V = np.concatenate([aV, frames[i - 1][1]], axis=1)
         np.testing.assert_allclose(st["O"], orc.frame_attn(queries[i], K, V, 0.3)[0], rtol=0, atol=1e-13)
+
+
+# ------------------------------------------------------------------- temporal rebase pins
+def test_rebase_composes_with_the_rotation_and_leaves_h_w_alone():
+    rng = np.random.default_rng(0)
+    sections, base = (8, 12, 12), 10000.0
+    x = rng.standard_normal((2, 9, 32))
+    pos = rng.integers(0, 200, size=(9, 3))
+    k = orc.rope3d(x, pos, sections, base)
+    k2, p2 = orc.rebase(k, pos, 12, sections, base)
+    shifted = pos.copy()
+    shifted[:, 0] -= 12
+    assert np.array_equal(p2, shifted)
+    np.testing.assert_allclose(k2, orc.rope3d(x, shifted, sections, base), rtol=0, atol=1e-12)
+    assert np.array_equal(k2[..., 8:], k[..., 8:])          # the h and w sections are untouched bit for bit
+    # attention logits of a query and a key that are rebased together do not change
+    q = orc.rope3d(rng.standard_normal((2, 4, 32)), np.array([[300, 5, 7]] * 4), sections, base)
+    q2 = orc.rope3d(orc.rope3d(q, np.array([[-300, -5, -7]] * 4), sections, base),
+                    np.array([[288, 5, 7]] * 4), sections, base)
+    np.testing.assert_allclose(orc.logits(q2[0], k2[0], 0.2), orc.logits(q[0], k[0], 0.2), rtol=0, atol=1e-11)
+
+
+def test_sliding_rollout_keeps_a_constant_temporal_horizon():
+    # sliding-window budgets with rebase: from the third step on the one retained frame sits
+    # two frame steps after the conditioning image and the queries three, whatever the step,
+    # and the result equals a cache built from scratch at those coordinates
+    case = synth.rolling_case(seed=4, n_steps=5, hq=2, hkv=1, gh=3, gw=4, n_text=4, n_score=12, dtype="f32")
+    n, t_scale = case.n_frame, 4
+    rot = (case.sections, case.base)
+    steps = orc.rolling_rollout(case.anchor_K, case.anchor_V, case.anchor_pos, case.anchor_segments, case.frames,
+                                case.queries, case.scale, lambda w: orc.budget_slide(n, w), rotate=rot,
+                                query_pos=case.query_pos, rebase_t_scale=t_scale)
+    aK = orc.rope3d(case.anchor_K, case.anchor_pos, *rot)
+    for i, st in enumerate(steps):
+        if i < 2:
+            assert st["shift"] == 0
+            continue
+        assert st["shift"] == t_scale * (i - 2)
+        frames = [s for s in st["segments"] if s[2] == orc.SEG_FRAME]
+        assert [s[1] for s in frames] == [0, n] and frames[1][3] == i   # the emptied frame leaves next step
+        Kf, Vf, pf = case.frames[i - 1]
+        want_pos = pf.copy()
+        want_pos[:, 0] = case.n_text + t_scale * 2           # frame "2" of the window
+        assert np.array_equal(st["pos"][0, -n:], want_pos)
+        K = np.concatenate([aK, orc.rope3d(Kf, want_pos, *rot)], axis=1)
+        np.testing.assert_allclose(st["K"], K, rtol=0, atol=1e-11)
+        qp = case.query_pos[i].copy()
+        qp[:, 0] = case.n_text + t_scale * 3                 # the frame being generated follows it
+        O, _ = orc.frame_attn(orc.rope3d(case.queries[i], qp, *rot), K, np.concatenate([case.anchor_V, Vf], axis=1),
+                              case.scale)
+        np.testing.assert_allclose(st["O"], O, rtol=0, atol=1e-10)
