@@ -107,6 +107,24 @@ int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride_h,
               const int32_t* pos, int sec_t, int sec_h, int sec_w, double base, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * pc_rebase -- temporal rebase of cached keys when the sliding window advances (Sec. 3.4,
+ * the rebase equation): pos_t <- pos_t - delta_t, pos_h and pos_w unchanged.  The cache
+ * holds keys that were rotated on insertion; rotations about one axis compose, so rows
+ * row0 .. row0+n_rows-1 of every KV head are turned by -delta_t on the temporal section
+ * (the first sec_t dims) only, in place, and delta_t is subtracted from the t coordinate of
+ * the same rows of pos.
+ *   K      dev, [Hkv][*][D], head stride k_stride_h (elements)
+ *   pos    dev, int32 [Hsel][*][3], head stride pos_stride_h (int32 elements)
+ *   delta_t  in position units (frames dropped x the temporal scale of Sec. 3.1)
+ * The temporal section must be a whole number of 16-byte chunks (sec_t % 8 == 0 for bf16,
+ * % 4 for fp32), else PC_ERR_UNSUPPORTED.  Enqueued on `stream`; no synchronisation.
+ * Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE, PC_ERR_UNSUPPORTED, PC_ERR_HIP.
+ */
+int pc_rebase(void* K, int dtype, int Hkv, int D, int64_t k_stride_h, int32_t* pos, int Hsel,
+              int64_t pos_stride_h, int row0, int n_rows, int delta_t, int sec_t, int sec_h, int sec_w,
+              double base, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * pc_score -- importance of every cached key: the softmax probability it receives
  * (Eq. 2 probabilities, softmax over ALL Nk keys presented), summed over the n_qs scoring
  * queries and over the query heads of its KV group.  The paper only asks for

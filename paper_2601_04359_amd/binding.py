@@ -12,7 +12,7 @@ from typing import Sequence
 __all__ = [
     "PC_F32", "PC_BF16", "PC_SEG_TEXT", "PC_SEG_COND", "PC_SEG_FRAME", "PC_SEG_SELF",
     "PC_BUDGET_POW", "PC_BUDGET_NORM", "PC_BUDGET_HALF", "PC_BUDGET_SLIDE", "PC_MAX_SEGMENTS",
-    "PackCacheError", "lib", "lib_path", "pc_version", "pc_strerror", "pc_budget", "pc_rope3d",
+    "PackCacheError", "lib", "lib_path", "pc_version", "pc_strerror", "pc_budget", "pc_rope3d", "pc_rebase",
     "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact",
     "pc_compact_workspace_bytes", "pc_compact_prepared", "pc_frame_attn", "pc_frame_attn_workspace_bytes",
     "segment_budgets",
@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
         L.pc_budget.argtypes = [C.c_int, C.c_int, C.c_int, C.c_double, C.c_int, i32p]
         L.pc_rope3d.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, i64, vp, C.c_int, C.c_int, C.c_int,
                                 C.c_double, vp]
+        L.pc_rebase.argtypes = [vp, C.c_int, C.c_int, C.c_int, i64, vp, C.c_int, i64, C.c_int, C.c_int, C.c_int,
+                                C.c_int, C.c_int, C.c_int, C.c_double, vp]
         L.pc_score_workspace_bytes.restype = sz
         L.pc_score_workspace_bytes.argtypes = [C.c_int] * 5
         L.pc_score.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i64, i64, vp,
@@ -146,6 +148,16 @@ def pc_rope3d(x, pos, sections: Sequence[int], base: float = 10000.0) -> None:
     _rows_dense(x, "x")
     _check(lib().pc_rope3d(x.data_ptr(), _dtype_code(x), H, n, D, x.stride(0), pos.data_ptr(),
                            int(sections[0]), int(sections[1]), int(sections[2]), float(base), _stream()))
+
+
+def pc_rebase(K, pos, row0: int, n_rows: int, delta_t: int, sections: Sequence[int], base: float = 10000.0) -> None:
+    """Rows row0 .. row0+n_rows-1 of K [Hkv][cap][D] and pos int32 [Hsel][cap][3]: temporal
+    coordinate lowered by delta_t, keys turned accordingly, in place."""
+    Hkv, _, D = K.shape
+    _rows_dense(K, "K")
+    _check(lib().pc_rebase(K.data_ptr(), _dtype_code(K), Hkv, D, K.stride(0), pos.data_ptr(), pos.shape[0],
+                           pos.stride(0), int(row0), int(n_rows), int(delta_t), int(sections[0]), int(sections[1]),
+                           int(sections[2]), float(base), _stream()))
 
 
 def pc_score_workspace_bytes(Hq: int, Hkv: int, n_qs: int, Nk: int, share_heads: bool = False) -> int:

@@ -13,6 +13,12 @@ A model that makes several attention passes per frame (iterative decoding) calls
 on the un-packed cache first, hands its log-sum-exp to refresh() and makes the remaining
 passes on the packed cache: the compaction is paid once per frame.
 
+With slide_t_scale set the window slides (Sec. 3.4, Slide-Cache): when a step begins, the
+oldest frames that the step before evicted completely leave the segment table and
+pc_rebase lowers the temporal coordinate of every retained frame row by slide_t_scale per
+dropped frame; `shift` is the total so far, and the caller places the frame it appends and
+its queries at their coordinates minus `shift`.
+
 Eviction is irreversible: a frame's candidates at one step are its survivors of the step
 before.  With mode "dense" nothing is evicted (the full-cache baseline); with mode "slide"
 only the newest frame survives (the sliding-window baseline of Sec. 3.3).
@@ -30,7 +36,8 @@ class RollingLayer:
 
     def __init__(self, Hq: int, Hkv: int, D: int, capacity: int, n_frame: int, scale: float,
                  mode: str = "pow", gamma: float = 0.85, b_min: int = 512, budget_tokens: int | None = None,
-                 n_score: int = 512, sections=(32, 48, 48), base: float = 10000.0, dtype=None, device="cuda:0"):
+                 n_score: int = 512, sections=(32, 48, 48), base: float = 10000.0, dtype=None, device="cuda:0",
+                 slide_t_scale: int | None = None):
         import torch
         if mode not in MODES:
             raise ValueError(f"mode {mode!r} not in {sorted(MODES)}")
@@ -45,6 +52,7 @@ class RollingLayer:
         self.pos = torch.empty((Hkv, capacity, 3), dtype=torch.int32, device=device)
         self.segments: list[tuple[int, int, int, int]] = []
         self.nk = 0
+        self.slide_t_scale, self.shift = slide_t_scale, 0
         n_rows = min(n_score, n_frame)
         self.q_rows = ((torch.arange(n_rows, dtype=torch.int64) * n_frame) // n_rows).to(torch.int32).to(device)
         if mode != "dense":   # the full-cache baseline neither scores nor compacts
@@ -70,6 +78,23 @@ class RollingLayer:
             pk.pc_rope3d(self.K[:, a:a + n], rotate_with, self.sections, self.base)
         self.segments.append((a, n, kind, frame))
         self.nk = a + n
+
+    def advance_window(self) -> int:
+        """Call when a step begins, before reserve(): drops the oldest frame segments that
+        are empty and rebases the retained frame rows.  Returns the total shift so far."""
+        if self.slide_t_scale is None:
+            return self.shift
+        first = next((j for j, s in enumerate(self.segments) if s[2] == pk.PC_SEG_FRAME), len(self.segments))
+        n_drop = 0
+        while first + n_drop < len(self.segments) and self.segments[first + n_drop][1] == 0:
+            n_drop += 1
+        if n_drop and first + n_drop < len(self.segments):
+            delta = self.slide_t_scale * n_drop
+            self.segments = self.segments[:first] + self.segments[first + n_drop:]
+            a = self.segments[first][0]
+            pk.pc_rebase(self.K, self.pos, a, self.nk - a, delta, self.sections, self.base)
+            self.shift += delta
+        return self.shift
 
     # ---- one frame step -----------------------------------------------------------------------
     def budgets(self) -> list[int]:

@@ -120,3 +120,71 @@ def test_attend_then_refresh_with_its_lse_keeps_the_same_rows():
         # the two scorings differ by the LSE's fp32 rounding: same kept rows on this seed
         assert torch.equal(a.pos[:, :a.nk], b.pos[:, :b.nk]) and torch.equal(a.K[:, :a.nk], b.K[:, :b.nk])
         assert torch.equal(Oa, Ob)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rebase_parity(dtype):
+    rng = np.random.default_rng(5)
+    hkv, cap, d, sections, base = 3, 700, 128, (32, 48, 48), 10000.0
+    K = rng.standard_normal((hkv, cap, d)).astype(np.float32)
+    if dtype == "bf16":
+        K = synth.to_bf16(K)
+    pos = rng.integers(0, 400, size=(hkv, cap, 3)).astype(np.int32)
+    Kd, pd = dev(K, dtype), dev(pos, None)
+    row0, n_rows, delta = 37, 601, 12
+    pk.pc_rebase(Kd, pd, row0, n_rows, delta, sections, base)
+    want_K, want_pos = orc.rebase(K[:, row0:row0 + n_rows], pos[:, row0:row0 + n_rows], delta, sections, base)
+    got = host(Kd).astype(np.float64)
+    tol = 2.0 ** -8 * np.abs(want_K) + 1e-6 if dtype == "bf16" else 1e-6
+    assert np.all(np.abs(got[:, row0:row0 + n_rows] - want_K) <= tol)
+    # rows outside the range, and the h / w sections inside it, keep their bits
+    assert np.array_equal(got[:, :row0], K[:, :row0]) and np.array_equal(got[:, row0 + n_rows:], K[:, row0 + n_rows:])
+    assert np.array_equal(got[:, :, 32:], K[:, :, 32:].astype(np.float64))
+    hp = host(pd)
+    assert np.array_equal(hp[:, row0:row0 + n_rows], want_pos)
+    assert np.array_equal(hp[:, :row0], pos[:, :row0]) and np.array_equal(hp[:, row0 + n_rows:], pos[:, row0 + n_rows:])
+
+
+@pytest.mark.parametrize("mode,b_min", [("half", 60), ("slide", 0), ("norm", 80)])
+def test_sliding_window_with_rebase_matches_oracle_fp32(mode, b_min):
+    # fp32 tier: the device's fp32 rotations and the oracle's fp64 ones differ by ~1e-7, far
+    # inside the selection band, so kept sets and coordinates must agree exactly step after
+    # step while rows are compared to 1e-5.
+    case = synth.rolling_case(seed=21, n_steps=7, hq=4, hkv=2, d=128, dtype="f32")
+    n, t_scale, gamma = case.n_frame, 4, 0.7
+    rot = (case.sections, case.base)
+    f32 = lambda a: np.asarray(a, dtype=np.float32).astype(np.float64)
+    want = orc.rolling_rollout(case.anchor_K, case.anchor_V, case.anchor_pos, case.anchor_segments, case.frames,
+                               case.queries, case.scale, _budget_fn(mode, case, gamma, b_min),
+                               score_rows=case.score_rows, rotate=rot, query_pos=case.query_pos,
+                               rebase_t_scale=t_scale, storage=f32)
+    assert want[-1]["shift"] > 0, "the case must slide"
+    layer = RollingLayer(case.Hq, case.Hkv, case.D, case.anchor_K.shape[1] + 3 * n, n, case.scale, mode=mode,
+                         gamma=gamma, b_min=b_min, n_score=case.score_rows.size, sections=case.sections,
+                         base=case.base, dtype=torch.float32, device=DEV, slide_t_scale=t_scale)
+    k, v, p = layer.reserve(case.anchor_K.shape[1])
+    k.copy_(dev(case.anchor_K, "f32")); v.copy_(dev(case.anchor_V, "f32"))
+    apos = dev(case.anchor_pos, None)
+    p.copy_(apos[None].expand_as(p))
+    for (start, length, kind, frame) in case.anchor_segments:
+        layer.commit(length, kind, frame, rotate_with=apos[start:start + length])
+    for i, Q in enumerate(case.queries):
+        shift = layer.advance_window()
+        assert shift == want[i]["shift"]
+        if i >= 1:
+            Kf, Vf, pf = case.frames[i - 1]
+            pf = pf.copy(); pf[:, 0] -= shift
+            k, v, p = layer.reserve(n)
+            k.copy_(dev(Kf, "f32")); v.copy_(dev(Vf, "f32"))
+            pfd = dev(pf, None)
+            p.copy_(pfd[None].expand_as(p))
+            layer.commit(n, pk.PC_SEG_FRAME, i, rotate_with=pfd)
+        qp = case.query_pos[i].copy(); qp[:, 0] -= shift
+        O = layer.step(dev(Q, "f32"), q_pos=dev(qp, None))
+        w = want[i]
+        assert layer.segments == w["segments"], (mode, i, layer.segments, w["segments"])
+        nk = layer.nk
+        assert np.array_equal(host(layer.pos[:, :nk]), w["pos"]), f"step {i + 1}: kept set or coordinates differ"
+        assert np.abs(host(layer.K[:, :nk]) - w["K"]).max() <= 1e-5
+        assert np.array_equal(host(layer.V[:, :nk]).astype(np.float64), w["V"])
+        assert np.abs(host(O) - w["O"]).max() <= 2e-5

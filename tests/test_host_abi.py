@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported(L):
     with open(os.path.join(ROOT, "include", "packcache.h")) as f:
         header = f.read()
     names = set(re.findall(r"\b(pc_[a-z0-9_]+)\s*\(", header))
-    assert {"pc_budget", "pc_rope3d", "pc_score", "pc_compact", "pc_frame_attn", "pc_compact_plan",
+    assert {"pc_budget", "pc_rope3d", "pc_rebase", "pc_score", "pc_compact", "pc_frame_attn", "pc_compact_plan",
             "pc_strerror", "pc_last_error_detail", "pc_version", "pc_score_workspace_bytes",
             "pc_compact_workspace_bytes", "pc_frame_attn_workspace_bytes"} <= names
     for n in names:
@@ -114,6 +114,12 @@ def test_argument_validation_returns_before_any_device_work(L):
     # rope: sections must add up to D
     assert L.pc_rope3d(one, 1, 1, 4, 128, 512, one, 32, 48, 40, 1e4, None) == -2
     assert L.pc_rope3d(None, 1, 1, 4, 128, 512, one, 32, 48, 48, 1e4, None) == -1
+    # rebase: sections must add up to D; a temporal section that is not whole 16-byte chunks; NULL
+    assert L.pc_rebase(one, 1, 1, 128, 512, one, 1, 12, 0, 4, 4, 32, 48, 40, 1e4, None) == -2
+    assert L.pc_rebase(one, 1, 1, 128, 512, one, 1, 12, 0, 4, 4, 20, 60, 48, 1e4, None) == -4
+    assert L.pc_rebase(None, 1, 1, 128, 512, one, 1, 12, 0, 4, 4, 32, 48, 48, 1e4, None) == -1
+    assert L.pc_rebase(one, 1, 1, 128, 512, one, 2, 12, 0, 4, 4, 32, 48, 48, 1e4, None) == -2   # Hsel > Hkv
+    assert L.pc_rebase(None, 1, 1, 128, 512, None, 1, 12, 0, 0, 4, 32, 48, 48, 1e4, None) == 0   # nothing to do
     # score: workspace missing / too small
     need = L.pc_score_workspace_bytes(4, 2, 8, 100, 0)
     assert need > 0
