@@ -193,6 +193,26 @@ int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,
                void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Cache mask (Sec. 3.1: a binary mask says which generated tokens are visible to later
+ * frames; Sec. 3.4: PackCache removes the masked positions instead of storing them).
+ * One flag per cached token, the same for every head: valid[j] != 0 keeps token j a
+ * candidate.  Two calls put the mask in front of pc_compact:
+ *   pc_masked_budgets  host only: budget_out[s] = min(budget[s], unmasked tokens of segment
+ *                      s) for FRAME segments, budget[s] otherwise.  valid is a HOST array
+ *                      covering every row the table names.
+ *   pc_mask_scores     device: score[h][j] = -1 where valid[j] == 0 (valid is a DEVICE array
+ *                      [Nk]), so that a masked token never outranks an unmasked one.
+ * pc_compact with the masked scores and budgets then keeps, per past frame, the
+ * top-budget unmasked tokens and physically removes the rest.  Anchors are not pruned and
+ * ignore the mask.
+ * Errors: PC_ERR_NULL, PC_ERR_SHAPE, PC_ERR_BUDGET, PC_ERR_HIP.
+ */
+int pc_masked_budgets(const pc_segment* seg, int n_seg, const int32_t* budget, const uint8_t* valid,
+                      int32_t* budget_out);
+int pc_mask_scores(float* score, int Hsel, int Nk, int64_t score_stride_h, const uint8_t* valid,
+                   void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * pc_frame_attn -- attention of one frame's queries over the keys presented (Eq. 2):
  * O = softmax(Q K^T * scale) V.  K is already rotated; for the current frame's queries
  * against anchors and earlier frames the causal mask of Eq. 2 hides nothing, so no mask

@@ -33,7 +33,7 @@ __all__ = [
     "bf16_bits_to_f64", "round_to_bf16", "f64",
     "budget_pow", "budget_norm", "budget_half", "budget_slide",
     "rope_angles", "rope3d", "rebase",
-    "logits", "softmax_rows", "score", "select_topk", "compact", "packed_segments",
+    "logits", "softmax_rows", "score", "select_topk", "compact", "packed_segments", "masked_budgets",
     "frame_attn", "frame_attn_bruteforce", "score_bruteforce", "rolling_rollout",
 ]
 
@@ -243,22 +243,38 @@ def packed_segments(segments, budgets):
     return out
 
 
-def compact(K, V, pos, sc, segments, budgets, share_heads: bool = False):
+def masked_budgets(segments, budgets, valid):
+    """Budgets under a cache mask (Sec. 3.1, the binary cache mask; Sec. 3.4: masked
+    positions are removed, not stored): a past frame can keep at most its unmasked tokens."""
+    valid = np.asarray(valid, dtype=bool)
+    return [min(b, int(valid[start:start + length].sum())) if kind == SEG_FRAME else b
+            for (start, length, kind, _), b in zip(segments, budgets)]
+
+
+def compact(K, V, pos, sc, segments, budgets, share_heads: bool = False, valid=None):
     """Keep, per selection head and per past-frame segment, the top-budget keys by
     score; remove everything else; keep chronological order and carry each kept row's
     (t, h, w) unchanged.  K, V: [Hkv][Nk][D]; pos: [Hsel][Nk][3]; sc: [Hsel][Nk].
     Hsel = 1 when share_heads (every KV head keeps the same rows) else Hkv.
+    valid ([Nk] bool, the cache mask, one flag per token for all heads): masked tokens of
+    a past frame are never candidates, whatever their score and the budget.
     Returns K', V' [Hkv][Nk'][D], pos' [Hsel][Nk'][3], idx [Hsel][Nk'], segments'."""
     K, V = np.asarray(K), np.asarray(V)
     pos, sc = np.asarray(pos), np.asarray(sc)
     hkv = K.shape[0]
     hsel = 1 if share_heads else hkv
     assert pos.shape[0] == hsel and sc.shape[0] == hsel
+    if valid is not None:
+        valid = np.asarray(valid, dtype=bool)
+        budgets = masked_budgets(segments, budgets, valid)
     idx = []
     for h in range(hsel):
         rows = []
         for (start, length, kind, _), b in zip(segments, budgets):
-            if kind == SEG_FRAME:
+            if kind == SEG_FRAME and valid is not None:
+                cand = np.flatnonzero(valid[start:start + length])          # unmasked tokens only
+                rows.append(start + cand[select_topk(sc[h, start + cand], min(cand.size, b))])
+            elif kind == SEG_FRAME:
                 rows.append(start + select_topk(sc[h, start:start + length], min(length, b)))
             else:
                 rows.append(np.arange(start, start + length, dtype=np.int64))

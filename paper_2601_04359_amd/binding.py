@@ -13,7 +13,7 @@ __all__ = [
     "PC_F32", "PC_BF16", "PC_SEG_TEXT", "PC_SEG_COND", "PC_SEG_FRAME", "PC_SEG_SELF",
     "PC_BUDGET_POW", "PC_BUDGET_NORM", "PC_BUDGET_HALF", "PC_BUDGET_SLIDE", "PC_MAX_SEGMENTS",
     "PackCacheError", "lib", "lib_path", "pc_version", "pc_strerror", "pc_budget", "pc_rope3d", "pc_rebase",
-    "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact",
+    "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact", "pc_masked_budgets", "pc_mask_scores",
     "pc_compact_workspace_bytes", "pc_compact_prepared", "pc_frame_attn", "pc_frame_attn_workspace_bytes",
     "segment_budgets",
 ]
@@ -65,6 +65,8 @@ def lib() -> C.CDLL:
         L.pc_score_workspace_bytes.argtypes = [C.c_int] * 5
         L.pc_score.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i64, i64, vp,
                                C.c_float, vp, i64, vp, i64, C.c_int, vp, sz, vp]
+        L.pc_masked_budgets.argtypes = [segp, C.c_int, i32p, vp, i32p]
+        L.pc_mask_scores.argtypes = [vp, C.c_int, C.c_int, i64, vp, vp]
         L.pc_compact_plan.argtypes = [segp, C.c_int, i32p, segp, i32p]
         L.pc_compact_workspace_bytes.restype = sz
         L.pc_compact_workspace_bytes.argtypes = [C.c_int] * 3
@@ -186,6 +188,23 @@ def pc_score(Qs, K, Nk: int, scale: float, lse=None, score=None, share_heads: bo
                           score.data_ptr(), score.stride(0),
                           int(share_heads), ws.data_ptr(), ws.numel(), _stream()))
     return score
+
+
+def pc_masked_budgets(segments, budgets, valid_host) -> list[int]:
+    """valid_host: host uint8 array (numpy) with one flag per cached row."""
+    import numpy as np
+    n = len(segments)
+    v = np.ascontiguousarray(valid_host, dtype=np.uint8)
+    b = (C.c_int32 * max(n, 1))(*[int(x) for x in budgets])
+    out = (C.c_int32 * max(n, 1))()
+    _check(lib().pc_masked_budgets(_seg_array(segments), n, b, v.ctypes.data, out))
+    return list(out[:n])
+
+
+def pc_mask_scores(score, valid) -> None:
+    """score fp32 [Hsel][Nk] (device), valid uint8 [Nk] (device): masked tokens get -1."""
+    _check(lib().pc_mask_scores(score.data_ptr(), score.shape[0], score.shape[1], score.stride(0),
+                                valid.data_ptr(), _stream()))
 
 
 def pc_compact_plan(segments, budgets):

@@ -406,6 +406,14 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   if (pdst >= 0) pos_o[pdst] = pval;
 }
 
+// score of a masked token -> -1: below every real score (sums of probabilities are >= 0), so
+// the select never prefers it to an unmasked token
+__global__ void mask_scores_kernel(float* __restrict__ score, int64_t score_stride_h, int Nk,
+                                   const uint8_t* __restrict__ valid) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j < Nk && valid[j] == 0) score[blockIdx.y * score_stride_h + j] = -1.f;
+}
+
 struct WsLayout {
   size_t idx_off, sync_off, flags_off, total;
   int chunks_per_head;
@@ -552,5 +560,18 @@ extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, in
   }
 #undef PC_LAUNCH_GATHER
   PC_CHECK_LAUNCH("pc_compact gather");
+  return PC_OK;
+}
+
+extern "C" int pc_mask_scores(float* score, int Hsel, int Nk, int64_t score_stride_h, const uint8_t* valid,
+                              void* stream) {
+  PC_REQUIRE(Hsel >= 0 && Nk >= 0, PC_ERR_SHAPE, "pc_mask_scores: Hsel=%d Nk=%d", Hsel, Nk);
+  if (Hsel == 0 || Nk == 0) return PC_OK;
+  PC_REQUIRE(score && valid, PC_ERR_NULL, "pc_mask_scores: score or valid is NULL");
+  PC_REQUIRE(Hsel == 1 || score_stride_h >= Nk, PC_ERR_SHAPE, "pc_mask_scores: score head stride %lld < Nk",
+             static_cast<long long>(score_stride_h));
+  mask_scores_kernel<<<dim3(ceil_div(Nk, 256), Hsel), 256, 0, static_cast<hipStream_t>(stream)>>>(
+      score, score_stride_h, Nk, valid);
+  PC_CHECK_LAUNCH("pc_mask_scores");
   return PC_OK;
 }

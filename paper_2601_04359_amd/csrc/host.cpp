@@ -270,3 +270,24 @@ extern "C" int pc_compact_plan(const pc_segment* seg_in, int n_seg, const int32_
   if (Nk_out) *Nk_out = static_cast<int32_t>(at_out);
   return PC_OK;
 }
+
+extern "C" int pc_masked_budgets(const pc_segment* seg, int n_seg, const int32_t* budget, const uint8_t* valid,
+                                 int32_t* budget_out) {
+  PC_REQUIRE(n_seg >= 0, PC_ERR_SHAPE, "pc_masked_budgets: n_seg=%d", n_seg);
+  PC_REQUIRE(n_seg == 0 || (seg && budget && valid && budget_out), PC_ERR_NULL,
+             "pc_masked_budgets: a pointer is NULL");
+  for (int s = 0; s < n_seg; ++s) {
+    const pc_segment& g = seg[s];
+    PC_REQUIRE(g.len >= 0 && g.start >= 0, PC_ERR_SHAPE, "pc_masked_budgets: segment %d (start %d, len %d)", s,
+               g.start, g.len);
+    int32_t b = budget[s];
+    if (g.kind == PC_SEG_FRAME) {
+      PC_REQUIRE(b >= 0, PC_ERR_BUDGET, "pc_masked_budgets: budget[%d]=%d is negative", s, b);
+      int32_t n_valid = 0;
+      for (int32_t i = 0; i < g.len; ++i) n_valid += valid[g.start + i] != 0;
+      b = std::min(b, n_valid);
+    }
+    budget_out[s] = b;
+  }
+  return PC_OK;
+}

@@ -413,3 +413,29 @@ def test_full_budget_packed_equals_dense_on_device():
     segs, nk = pk.pc_compact(K, V, pos, sc, w.segments, [s[1] for s in w.segments])
     assert nk == w.Nk and segs == w.segments
     assert torch.equal(pk.pc_frame_attn(Q, K, V, nk, w.scale), O_dense)
+
+
+@pytest.mark.parametrize("in_place", [False, True])
+def test_cache_mask_in_front_of_the_select(in_place):
+    # masked tokens are never kept and are physically removed, also from frames within budget
+    w = synth.midsize()
+    rng = np.random.default_rng(8)
+    valid = rng.random(w.Nk) < 0.4
+    sco = orc.score(w.Q[:, w.score_rows], w.K, w.scale)
+    budgets = budgets_for(w)
+    want = orc.compact(w.K, w.V, np.broadcast_to(w.pos_k[None], (w.Hkv, w.Nk, 3)), sco, w.segments, budgets,
+                       valid=valid)
+    mb = pk.pc_masked_budgets(w.segments, budgets, valid.astype(np.uint8))
+    assert mb == orc.masked_budgets(w.segments, budgets, valid)
+    sc = dev(sco.astype(np.float32), None)
+    pk.pc_mask_scores(sc, dev(valid.astype(np.uint8), None))
+    assert np.array_equal(host(sc) == -1.0, np.broadcast_to(~valid[None], sco.shape))
+    Kp, Vp, pp, idx, segs = _compact_run(w, host(sc), mb, in_place)
+    assert segs == want[4] and Kp.shape[1] == want[0].shape[1]
+    # selection on the fp32 image of the oracle's scores: exact up to fp32 ties
+    sel_sc = np.where(valid[None], sco.astype(np.float32).astype(np.float64), -1.0)
+    check_selection(idx, sel_sc, w.segments, mb)
+    for h in range(w.Hkv):
+        assert np.all(valid[idx[h]] | (idx[h] < w.segments[2][0]))
+        assert np.array_equal(Kp[h], w.K[h][idx[h]]) and np.array_equal(Vp[h], w.V[h][idx[h]])
+        assert np.array_equal(pp[h], w.pos_k[idx[h]])

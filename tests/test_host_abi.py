@@ -141,3 +141,14 @@ def test_binding_raises_without_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "lib_path", lambda: str(tmp_path / "libpackcache.so"))
     with pytest.raises(FileNotFoundError):
         binding.pc_version()
+
+
+def test_masked_budgets_match_the_oracle():
+    w = synth.midsize()
+    rng = np.random.default_rng(0)
+    valid = (rng.random(w.Nk) < 0.3).astype(np.uint8)
+    for gamma, b_min in ((0.85, 32), (0.5, 0), (1.0, 0)):
+        budgets = pk.segment_budgets(w.segments, orc.budget_pow(w.n_frame, w.n_past, gamma, b_min))
+        assert pk.pc_masked_budgets(w.segments, budgets, valid) == orc.masked_budgets(w.segments, budgets, valid)
+    with pytest.raises(pk.PackCacheError):
+        pk.pc_masked_budgets(w.segments, [-1] * len(w.segments), valid)

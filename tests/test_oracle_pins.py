@@ -528,3 +528,31 @@ def test_sliding_rollout_keeps_a_constant_temporal_horizon():
         O, _ = orc.frame_attn(orc.rope3d(case.queries[i], qp, *rot), K, np.concatenate([case.anchor_V, Vf], axis=1),
                               case.scale)
         np.testing.assert_allclose(st["O"], O, rtol=0, atol=1e-10)
+
+
+# ------------------------------------------------------------------- cache mask pins
+def test_cache_mask_never_keeps_a_masked_token_and_equals_deleting_them_first():
+    w, sc, budgets, _ = _compact_c1()
+    rng = np.random.default_rng(3)
+    valid = rng.random(w.Nk) < 0.5
+    Kp, Vp, pp, idx, segs = orc.compact(w.K, w.V, w.pos_k[None], sc, w.segments, budgets, valid=valid)
+    frame_rows = np.zeros(w.Nk, bool)
+    for (start, length, kind, _) in w.segments:
+        if kind == orc.SEG_FRAME:
+            frame_rows[start:start + length] = True
+    assert np.all(valid[idx[0]] | ~frame_rows[idx[0]])                      # masked frame tokens are gone
+    assert [s[1] for s in segs] == orc.masked_budgets(w.segments, [min(b, s[1]) for b, s in zip(budgets, w.segments)], valid)
+    # same result as deleting the masked frame rows first and compacting what is left
+    keep = valid | ~frame_rows
+    rows = np.flatnonzero(keep)
+    segs2, at = [], 0
+    for (start, length, kind, fr) in w.segments:
+        m = int(keep[start:start + length].sum())
+        segs2.append((at, m, kind, fr))
+        at += m
+    K2, V2, p2, idx2, segs3 = orc.compact(w.K[:, rows], w.V[:, rows], w.pos_k[None][:, rows], sc[:, rows], segs2, budgets)
+    assert segs3 == segs and np.array_equal(K2, Kp) and np.array_equal(p2, pp) and np.array_equal(rows[idx2[0]], idx[0])
+    # an all-ones mask changes nothing
+    full = orc.compact(w.K, w.V, w.pos_k[None], sc, w.segments, budgets, valid=np.ones(w.Nk, bool))
+    base = orc.compact(w.K, w.V, w.pos_k[None], sc, w.segments, budgets)
+    assert np.array_equal(full[3], base[3]) and full[4] == base[4]
