@@ -193,6 +193,28 @@ int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,
                void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * pc_compact_batch -- pc_compact for n_layers layers at once (the caches of a layer stack are
+ * re-packed together at a frame-step boundary): one select launch and one gather launch
+ * cover every layer, so the small per-layer launches neither queue behind each other nor
+ * leave the chip part empty.  Layer l of every tensor starts *_stride_l elements after
+ * layer l-1 (K, V: elements of dtype; pos, idx: int32; score: fp32); everything else is as
+ * in pc_compact and is the same for all layers: one segment table, one budget per segment
+ * (budgets depend on the temporal distance only), one dtype, Hkv and D.  n_layers = 1 with
+ * zero layer strides is pc_compact.  In place, n_layers * Hkv must not exceed 256.
+ * The workspace is sized by pc_compact_batch_workspace_bytes.
+ */
+size_t pc_compact_batch_workspace_bytes(int n_layers, int Hkv, int Nk_in, int share_heads);
+int pc_compact_batch(int n_layers, void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,
+                     int64_t kv_stride_h, int64_t kv_stride_l, int64_t pos_stride_h,
+                     int64_t pos_stride_l, const float* score, int64_t score_stride_h,
+                     int64_t score_stride_l, const pc_segment* seg_in, int n_seg,
+                     const int32_t* budget, int share_heads, void* K_out, void* V_out,
+                     int32_t* pos_out, int64_t kv_out_stride_h, int64_t kv_out_stride_l,
+                     int64_t pos_out_stride_h, int64_t pos_out_stride_l, int32_t* idx_out,
+                     int64_t idx_stride_h, int64_t idx_stride_l, pc_segment* seg_out,
+                     int32_t* Nk_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Cache mask (Sec. 3.1: a binary mask says which generated tokens are visible to later
  * frames; Sec. 3.4: PackCache removes the masked positions instead of storing them).
  * One flag per cached token, the same for every head: valid[j] != 0 keeps token j a

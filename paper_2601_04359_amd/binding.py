@@ -13,7 +13,7 @@ __all__ = [
     "PC_F32", "PC_BF16", "PC_SEG_TEXT", "PC_SEG_COND", "PC_SEG_FRAME", "PC_SEG_SELF",
     "PC_BUDGET_POW", "PC_BUDGET_NORM", "PC_BUDGET_HALF", "PC_BUDGET_SLIDE", "PC_MAX_SEGMENTS",
     "PackCacheError", "lib", "lib_path", "pc_version", "pc_strerror", "pc_budget", "pc_rope3d", "pc_rebase",
-    "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact", "pc_masked_budgets", "pc_mask_scores",
+    "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact", "pc_compact_batch", "pc_compact_batch_workspace_bytes", "pc_masked_budgets", "pc_mask_scores",
     "pc_compact_workspace_bytes", "pc_compact_prepared", "pc_frame_attn", "pc_frame_attn_workspace_bytes",
     "segment_budgets",
 ]
@@ -65,6 +65,11 @@ def lib() -> C.CDLL:
         L.pc_score_workspace_bytes.argtypes = [C.c_int] * 5
         L.pc_score.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i64, i64, vp,
                                C.c_float, vp, i64, vp, i64, C.c_int, vp, sz, vp]
+        L.pc_compact_batch_workspace_bytes.restype = sz
+        L.pc_compact_batch_workspace_bytes.argtypes = [C.c_int] * 4
+        L.pc_compact_batch.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, i64, i64, i64, i64, vp, i64,
+                                       i64, segp, C.c_int, i32p, C.c_int, vp, vp, vp, i64, i64, i64, i64, vp, i64,
+                                       i64, segp, i32p, vp, sz, vp]
         L.pc_masked_budgets.argtypes = [segp, C.c_int, i32p, vp, i32p]
         L.pc_mask_scores.argtypes = [vp, C.c_int, C.c_int, i64, vp, vp]
         L.pc_compact_plan.argtypes = [segp, C.c_int, i32p, segp, i32p]
@@ -241,6 +246,35 @@ def pc_compact(K, V, pos, score, segments, budgets, share_heads: bool = False, o
                             Ko.data_ptr(), Vo.data_ptr(), po.data_ptr(), Ko.stride(0), po.stride(0),
                             _ptr(idx), 0 if idx is None else idx.stride(0), seg_out, C.byref(nk),
                             ws.data_ptr(), ws.numel(), _stream()))
+    return [(s.start, s.len, s.kind, s.frame) for s in seg_out[:n]], nk.value
+
+
+def pc_compact_batch_workspace_bytes(n_layers: int, Hkv: int, Nk_in: int, share_heads: bool = False) -> int:
+    return lib().pc_compact_batch_workspace_bytes(n_layers, Hkv, Nk_in, int(share_heads))
+
+
+def pc_compact_batch(K, V, pos, score, segments, budgets, share_heads: bool = False, out=None, idx=None, ws=None):
+    """pc_compact over a stack of layers in one call: K, V [L][Hkv][cap][D], pos int32
+    [L][Hsel][cap][3], score fp32 [L][Hsel][>=Nk]; out / idx as in pc_compact with a leading
+    layer axis.  Returns (segments_out, Nk_out)."""
+    L, Hkv, _, D = K.shape
+    _rows_dense(K, "K")
+    _rows_dense(V, "V")
+    n = len(segments)
+    nk_in = segments[-1][0] + segments[-1][1] if n else 0
+    seg_out = (pc_segment * max(n, 1))()
+    b = (C.c_int32 * max(n, 1))(*[int(v) for v in budgets])
+    nk = C.c_int32(0)
+    Ko, Vo, po = (K, V, pos) if out is None else out
+    if ws is None:
+        ws = _workspace(pc_compact_batch_workspace_bytes(L, Hkv, nk_in, share_heads), K)
+    _check(lib().pc_compact_batch(L, K.data_ptr(), V.data_ptr(), pos.data_ptr(), _dtype_code(K), Hkv, D,
+                                  K.stride(1), K.stride(0), pos.stride(1), pos.stride(0), score.data_ptr(),
+                                  score.stride(1), score.stride(0), _seg_array(segments), n, b, int(share_heads),
+                                  Ko.data_ptr(), Vo.data_ptr(), po.data_ptr(), Ko.stride(1), Ko.stride(0),
+                                  po.stride(1), po.stride(0), _ptr(idx), 0 if idx is None else idx.stride(1),
+                                  0 if idx is None else idx.stride(0), seg_out, C.byref(nk), ws.data_ptr(),
+                                  ws.numel(), _stream()))
     return [(s.start, s.len, s.kind, s.frame) for s in seg_out[:n]], nk.value
 
 

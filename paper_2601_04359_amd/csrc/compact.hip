@@ -109,16 +109,18 @@ __device__ void select_wave(const float* __restrict__ sc, int len, int k, int32_
 template <int kItems>
 __global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ score,
                                                     int64_t score_stride_h, int32_t* __restrict__ idx,
-                                                    int64_t idx_stride_h, SegTable tab) {
-  const int s = blockIdx.x, h = blockIdx.y;
+                                                    int64_t idx_stride_h, SegTable tab, int hsel,
+                                                    int64_t score_stride_l, int64_t idx_stride_l) {
+  const int s = blockIdx.x, h = blockIdx.y;  // h runs over layers x selection heads
+  const int64_t sc_off = (h / hsel) * score_stride_l + (h % hsel) * score_stride_h;
   const int start = tab.start[s], len = tab.len[s], keep = tab.keep[s];
-  int32_t* out = idx + h * idx_stride_h + tab.dst[s];
+  int32_t* out = idx + (h / hsel) * idx_stride_l + (h % hsel) * idx_stride_h + tab.dst[s];
   if (keep <= 0) return;
   if (!tab.prune[s]) {  // anchors, current frame, or a frame within budget: keep every row
     for (int e = threadIdx.x; e < len; e += 64) out[e] = start + e;
     return;
   }
-  select_wave<kItems>(score + h * score_stride_h + start, len, keep, out, start);
+  select_wave<kItems>(score + sc_off + start, len, keep, out, start);
 }
 
 // Four waves per segment: wave w owns the contiguous slice [w * 64 kItems, (w+1) * 64 kItems)
@@ -137,7 +139,8 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
                                                            int64_t score_stride_h,
                                                            int32_t* __restrict__ idx, int64_t idx_stride_h,
                                                            SegTable tab, int32_t* __restrict__ clear,
-                                                           int n_clear) {
+                                                           int n_clear, int hsel, int64_t score_stride_l,
+                                                           int64_t idx_stride_l) {
   constexpr int kCopies = 32;
   __shared__ __align__(16) int s_hist[256 * kCopies];
   __shared__ int s_wave_sum[4];
@@ -149,13 +152,13 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
     for (int i = b * 256 + threadIdx.x; i < n_clear; i += nb * 256) clear[i] = 0;
   }
   const int start = tab.start[s], len = tab.len[s], k = tab.keep[s];
-  int32_t* out = idx + h * idx_stride_h + tab.dst[s];
+  int32_t* out = idx + (h / hsel) * idx_stride_l + (h % hsel) * idx_stride_h + tab.dst[s];
   if (k <= 0) return;  // block-uniform
   if (!tab.prune[s]) {
     for (int e = threadIdx.x; e < len; e += 256) out[e] = start + e;
     return;
   }
-  const float* sc = score + h * score_stride_h + start;
+  const float* sc = score + (h / hsel) * score_stride_l + (h % hsel) * score_stride_h + start;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   const int base = wave * 64 * kItems;
@@ -276,8 +279,8 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
 }
 
 // ---- gather ----------------------------------------------------------------------------------
-constexpr int kMaxTicketHeads = 64;
-struct GatherSync {  // one ticket counter per KV head, each on its own 128-byte line
+constexpr int kMaxTicketHeads = 256;  // layers x KV heads of one call
+struct GatherSync {  // one ticket counter per (layer, KV head), each on its own 128-byte line
   int32_t abort;
   int32_t pad[31];
   int32_t ticket[kMaxTicketHeads][32];
@@ -295,19 +298,25 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     const int32_t* __restrict__ idx, int64_t idx_stride_h, int share_heads, int Hkv, int Nk_in, int Nk_out,
     int64_t in_stride_c, int64_t out_stride_c,
     int64_t pos_stride_h, int64_t pos_out_stride_h, GatherSync* sync, int32_t* flags,
-    int chunks_per_head, SegTable tab) {
+    int chunks_per_head, SegTable tab, int n_layers, int64_t in_stride_lc, int64_t out_stride_lc,
+    int64_t pos_stride_l, int64_t pos_out_stride_l, int64_t idx_stride_l) {
   __shared__ int s_ticket;
-  const int h = blockIdx.x % Hkv;
-  int cc = blockIdx.x / Hkv;
+  const int n_vh = Hkv * n_layers;       // (layer, KV head) pairs
+  const int vh = blockIdx.x % n_vh;
+  const int l = vh / Hkv, h = vh % Hkv;
+  int cc = blockIdx.x / n_vh;
   if constexpr (kInPlace) {  // chunks of a head are taken in ticket order, not in launch order
-    if (threadIdx.x == 0) s_ticket = atomicAdd(&sync->ticket[h][0], 1);
+    if (threadIdx.x == 0) s_ticket = atomicAdd(&sync->ticket[vh][0], 1);
     __syncthreads();
     cc = s_ticket;
   }
   const int hs = share_heads ? 0 : h;
   const int r0 = cc * kRows;
   const int r1 = min(r0 + kRows, Nk_out);
-  const int32_t* idx_h = idx + hs * idx_stride_h;
+  const int32_t* idx_h = idx + l * idx_stride_l + hs * idx_stride_h;
+  const int64_t in_base = l * in_stride_lc + h * in_stride_c, out_base = l * out_stride_lc + h * out_stride_c;
+  const int64_t pos_in_base = l * pos_stride_l + hs * pos_stride_h;
+  const int64_t pos_out_base = l * pos_out_stride_l + hs * pos_out_stride_h;
 
   // ---- load: a thread moves one 16-byte chunk of a K row and the same chunk of its V row ----
   constexpr int kRowsPerPass = kGatherThreads / cpr;
@@ -322,10 +331,10 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     if (row < r1) {
       const int src = min(max(idx_h[row], 0), Nk_in - 1);  // a valid table never needs the clamp
       if (!kInPlace || src != row) {
-        const int64_t so = h * in_stride_c + static_cast<int64_t>(src) * cpr + ch;
+        const int64_t so = in_base + static_cast<int64_t>(src) * cpr + ch;
         kval[it] = K[so];
         vval[it] = V[so];
-        dst_off[it] = h * out_stride_c + static_cast<int64_t>(row) * cpr + ch;
+        dst_off[it] = out_base + static_cast<int64_t>(row) * cpr + ch;
       }
     }
   }
@@ -336,8 +345,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     const int row = r0 + threadIdx.x / 3, comp = threadIdx.x % 3;
     const int src = min(max(idx_h[row], 0), Nk_in - 1);
     if (!kInPlace || src != row) {
-      pval = pos[hs * pos_stride_h + static_cast<int64_t>(src) * 3 + comp];
-      pdst = hs * pos_out_stride_h + static_cast<int64_t>(row) * 3 + comp;
+      pval = pos[pos_in_base + static_cast<int64_t>(src) * 3 + comp];
+      pdst = pos_out_base + static_cast<int64_t>(row) * 3 + comp;
     }
   }
 
@@ -352,7 +361,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     for (int it = 0; it < kPasses; ++it) asm volatile("" : "+v"(kval[it]), "+v"(vval[it]));
     asm volatile("" : "+v"(pval));
     __syncthreads();
-    int32_t* flags_h = flags + h * chunks_per_head;
+    int32_t* flags_h = flags + static_cast<int64_t>(vh) * chunks_per_head;
     if (threadIdx.x == 0)
       __hip_atomic_store(&flags_h[cc], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // Source row of the i-th kept row of a segment: start + i <= src <= start + (len - keep) + i.
@@ -419,17 +428,17 @@ struct WsLayout {
   int chunks_per_head;
 };
 
-WsLayout ws_layout(int Hkv, int Nk_in, int share_heads) {
+WsLayout ws_layout(int n_layers, int Hkv, int Nk_in, int share_heads) {
   WsLayout w;
   const int hsel = share_heads ? 1 : Hkv;
   size_t at = 0;
   w.idx_off = at;
-  at += align_up(sizeof(int32_t) * static_cast<size_t>(hsel) * Nk_in, 256);
+  at += align_up(sizeof(int32_t) * static_cast<size_t>(n_layers) * hsel * Nk_in, 256);
   w.sync_off = at;
   at += sizeof(GatherSync);
   w.flags_off = at;
   w.chunks_per_head = ceil_div(Nk_in, kGatherRows);
-  at += align_up(sizeof(int32_t) * static_cast<size_t>(Hkv) * w.chunks_per_head, 256);
+  at += align_up(sizeof(int32_t) * static_cast<size_t>(n_layers) * Hkv * w.chunks_per_head, 256);
   w.total = at;
   return w;
 }
@@ -441,7 +450,12 @@ using namespace pc;
 
 extern "C" size_t pc_compact_workspace_bytes(int Hkv, int Nk_in, int share_heads) {
   if (Hkv <= 0 || Nk_in <= 0) return 0;
-  return ws_layout(Hkv, Nk_in, share_heads).total;
+  return ws_layout(1, Hkv, Nk_in, share_heads).total;
+}
+
+extern "C" size_t pc_compact_batch_workspace_bytes(int n_layers, int Hkv, int Nk_in, int share_heads) {
+  if (n_layers <= 0 || Hkv <= 0 || Nk_in <= 0) return 0;
+  return ws_layout(n_layers, Hkv, Nk_in, share_heads).total;
 }
 
 extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,
@@ -451,8 +465,22 @@ extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, in
                           int32_t* pos_out, int64_t kv_out_stride_h, int64_t pos_out_stride_h,
                           int32_t* idx_out, int64_t idx_stride_h, pc_segment* seg_out,
                           int32_t* Nk_out, void* ws, size_t ws_bytes, void* stream) {
+  return pc_compact_batch(1, K, V, pos, dtype, Hkv, D, kv_stride_h, 0, pos_stride_h, 0, score, score_stride_h, 0,
+                          seg_in, n_seg, budget, share_heads, K_out, V_out, pos_out, kv_out_stride_h, 0,
+                          pos_out_stride_h, 0, idx_out, idx_stride_h, 0, seg_out, Nk_out, ws, ws_bytes, stream);
+}
+
+extern "C" int pc_compact_batch(int n_layers, void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,
+                                int64_t kv_stride_h, int64_t kv_stride_l, int64_t pos_stride_h,
+                                int64_t pos_stride_l, const float* score, int64_t score_stride_h,
+                                int64_t score_stride_l, const pc_segment* seg_in, int n_seg,
+                                const int32_t* budget, int share_heads, void* K_out, void* V_out,
+                                int32_t* pos_out, int64_t kv_out_stride_h, int64_t kv_out_stride_l,
+                                int64_t pos_out_stride_h, int64_t pos_out_stride_l, int32_t* idx_out,
+                                int64_t idx_stride_h, int64_t idx_stride_l, pc_segment* seg_out,
+                                int32_t* Nk_out, void* ws, size_t ws_bytes, void* stream) {
   PC_REQUIRE(dtype == PC_F32 || dtype == PC_BF16, PC_ERR_DTYPE, "pc_compact: dtype %d", dtype);
-  PC_REQUIRE(Hkv > 0 && D > 0, PC_ERR_SHAPE, "pc_compact: Hkv=%d D=%d", Hkv, D);
+  PC_REQUIRE(Hkv > 0 && D > 0 && n_layers >= 1, PC_ERR_SHAPE, "pc_compact: layers=%d Hkv=%d D=%d", n_layers, Hkv, D);
   PC_REQUIRE(n_seg >= 0 && n_seg <= PC_MAX_SEGMENTS, PC_ERR_SHAPE,
              "pc_compact: n_seg=%d outside [0, %d]", n_seg, PC_MAX_SEGMENTS);
   pc_segment plan[PC_MAX_SEGMENTS];
@@ -474,7 +502,8 @@ extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, in
   const bool in_place = K_out == K;
   PC_REQUIRE((V_out == V) == in_place && (pos_out == pos) == in_place, PC_ERR_SHAPE,
              "pc_compact: outputs must alias the inputs all together or not at all");
-  PC_REQUIRE(!in_place || (kv_out_stride_h == kv_stride_h && pos_out_stride_h == pos_stride_h),
+  PC_REQUIRE(!in_place || (kv_out_stride_h == kv_stride_h && pos_out_stride_h == pos_stride_h &&
+                           kv_out_stride_l == kv_stride_l && pos_out_stride_l == pos_stride_l),
              PC_ERR_SHAPE, "pc_compact: in-place compaction needs equal input and output strides");
   const int hsel = share_heads ? 1 : Hkv;
   PC_REQUIRE(kv_stride_h >= static_cast<int64_t>(nk_in) * D && kv_out_stride_h >= static_cast<int64_t>(nk_out) * D,
@@ -486,9 +515,21 @@ extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, in
              "pc_compact: idx head stride %lld < Nk_out", static_cast<long long>(idx_stride_h));
   const uintptr_t al = reinterpret_cast<uintptr_t>(K) | reinterpret_cast<uintptr_t>(V) |
                        reinterpret_cast<uintptr_t>(K_out) | reinterpret_cast<uintptr_t>(V_out);
-  PC_REQUIRE(al % 16 == 0 && (kv_stride_h * elt) % 16 == 0 && (kv_out_stride_h * elt) % 16 == 0,
-             PC_ERR_SHAPE, "pc_compact: K/V buffers and head strides must be 16-byte aligned");
-  const WsLayout lay = ws_layout(Hkv, nk_in, share_heads);
+  PC_REQUIRE(al % 16 == 0 && (kv_stride_h * elt) % 16 == 0 && (kv_out_stride_h * elt) % 16 == 0 &&
+                 (kv_stride_l * elt) % 16 == 0 && (kv_out_stride_l * elt) % 16 == 0,
+             PC_ERR_SHAPE, "pc_compact: K/V buffers and head / layer strides must be 16-byte aligned");
+  if (n_layers > 1) {
+    PC_REQUIRE(kv_stride_l >= kv_stride_h * (Hkv - 1) + static_cast<int64_t>(nk_in) * D &&
+                   kv_out_stride_l >= kv_out_stride_h * (Hkv - 1) + static_cast<int64_t>(nk_out) * D &&
+                   pos_stride_l >= pos_stride_h * (hsel - 1) + static_cast<int64_t>(nk_in) * 3 &&
+                   pos_out_stride_l >= pos_out_stride_h * (hsel - 1) + static_cast<int64_t>(nk_out) * 3 &&
+                   score_stride_l >= score_stride_h * (hsel - 1) + nk_in &&
+                   (idx_out == nullptr || idx_stride_l >= idx_stride_h * (hsel - 1) + nk_out),
+               PC_ERR_SHAPE, "pc_compact_batch: a layer stride is smaller than one layer");
+    PC_REQUIRE(!in_place || n_layers * Hkv <= kMaxTicketHeads, PC_ERR_UNSUPPORTED,
+               "pc_compact_batch: in place supports at most %d (layer, KV head) pairs per call", kMaxTicketHeads);
+  }
+  const WsLayout lay = ws_layout(n_layers, Hkv, nk_in, share_heads);
   PC_REQUIRE(ws != nullptr && ws_bytes >= lay.total, PC_ERR_WORKSPACE,
              "pc_compact: workspace %zu bytes, need %zu", ws_bytes, lay.total);
   PC_REQUIRE(reinterpret_cast<uintptr_t>(ws) % 16 == 0, PC_ERR_WORKSPACE, "pc_compact: workspace not 16-byte aligned");
@@ -513,22 +554,27 @@ extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, in
   uint8_t* wsb = static_cast<uint8_t*>(ws);
   int32_t* idx = idx_out ? idx_out : reinterpret_cast<int32_t*>(wsb + lay.idx_off);
   const int64_t idx_stride = idx_out ? idx_stride_h : nk_in;
+  const int64_t idx_stride_layer = idx_out ? idx_stride_l : static_cast<int64_t>(hsel) * nk_in;
   GatherSync* sync = reinterpret_cast<GatherSync*>(wsb + lay.sync_off);
   int32_t* flags = reinterpret_cast<int32_t*>(wsb + lay.flags_off);
 
-  const dim3 sgrid(n_seg, hsel);
+  const dim3 sgrid(n_seg, hsel * n_layers);
   // the select kernel also clears the in-place gather's counters and flags (contiguous in ws)
   int32_t* clear = in_place ? reinterpret_cast<int32_t*>(sync) : nullptr;
   const int n_clear = in_place ? static_cast<int>((lay.total - lay.sync_off) / sizeof(int32_t)) : 0;
   if (max_prune_len <= 256)
-    select_block_kernel<1><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear);
+    select_block_kernel<1><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear, hsel,
+                                                   score_stride_l, idx_stride_layer);
   else if (max_prune_len <= 1024)
-    select_block_kernel<4><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear);
+    select_block_kernel<4><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear, hsel,
+                                                   score_stride_l, idx_stride_layer);
   else if (max_prune_len <= PC_MAX_SELECT_LEN)
-    select_block_kernel<16><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear);
+    select_block_kernel<16><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear, hsel,
+                                                   score_stride_l, idx_stride_layer);
   else
   {
-    select_kernel<0><<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab);
+    select_kernel<0><<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, hsel, score_stride_l,
+                                           idx_stride_layer);
     if (in_place) {
       PC_CHECK_LAUNCH("pc_compact select");
       clear_words<<<ceil_div(n_clear, 256), 256, 0, st>>>(clear, n_clear);
@@ -541,16 +587,16 @@ extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, in
   const int rows_per_group = in_place ? kRowsInPlace : kGatherRows;
   const int chunks_per_head = ceil_div(nk_out, rows_per_group);
   const int64_t in_stride_c = kv_stride_h * elt / 16, out_stride_c = kv_out_stride_h * elt / 16;
-  const dim3 ggrid(chunks_per_head * Hkv);
-  if (in_place) {
-    PC_REQUIRE(Hkv <= kMaxTicketHeads, PC_ERR_UNSUPPORTED, "pc_compact: in place supports at most %d KV heads",
-               kMaxTicketHeads);
-  }
+  const dim3 ggrid(chunks_per_head * Hkv * n_layers);
+  PC_REQUIRE(!in_place || Hkv * n_layers <= kMaxTicketHeads, PC_ERR_UNSUPPORTED,
+             "pc_compact: in place supports at most %d (layer, KV head) pairs", kMaxTicketHeads);
+  const int64_t in_stride_lc = kv_stride_l * elt / 16, out_stride_lc = kv_out_stride_l * elt / 16;
 #define PC_LAUNCH_GATHER(CPR, ROWS, INPLACE)                                                             \
   gather_kernel<CPR, ROWS, INPLACE><<<ggrid, kGatherThreads, 0, st>>>(                                   \
       static_cast<const u32x4*>(K), static_cast<const u32x4*>(V), pos, static_cast<u32x4*>(K_out),       \
       static_cast<u32x4*>(V_out), pos_out, idx, idx_stride, share_heads, Hkv, nk_in, nk_out, in_stride_c, \
-      out_stride_c, pos_stride_h, pos_out_stride_h, sync, flags, lay.chunks_per_head, tab)
+      out_stride_c, pos_stride_h, pos_out_stride_h, sync, flags, lay.chunks_per_head, tab, n_layers,      \
+      in_stride_lc, out_stride_lc, pos_stride_l, pos_out_stride_l, idx_stride_layer)
   if (cpr == 16) {
     if (in_place) PC_LAUNCH_GATHER(16, kRowsInPlace, true); else PC_LAUNCH_GATHER(16, kGatherRows, false);
   } else if (cpr == 32) {

@@ -439,3 +439,46 @@ def test_cache_mask_in_front_of_the_select(in_place):
         assert np.all(valid[idx[h]] | (idx[h] < w.segments[2][0]))
         assert np.array_equal(Kp[h], w.K[h][idx[h]]) and np.array_equal(Vp[h], w.V[h][idx[h]])
         assert np.array_equal(pp[h], w.pos_k[idx[h]])
+
+
+@pytest.mark.parametrize("share", [False, True])
+@pytest.mark.parametrize("in_place", [False, True])
+def test_compact_batch_equals_layer_by_layer_and_the_oracle(in_place, share):
+    # a stack of layers re-packed in one call: same rows, bit for bit, as one call per layer
+    ws_ = [synth.midsize(seed=30 + l) for l in range(3)]
+    w = ws_[0]
+    hsel = 1 if share else w.Hkv
+    cap = w.Nk + 17                                              # spare capacity: strides differ from sizes
+    K = torch.zeros((3, w.Hkv, cap, w.D), dtype=torch.bfloat16, device=DEV)
+    V = torch.zeros_like(K)
+    pos = torch.zeros((3, hsel, cap, 3), dtype=torch.int32, device=DEV)
+    sc = torch.zeros((3, hsel, cap), dtype=torch.float32, device=DEV)
+    sco = []
+    for l, wl in enumerate(ws_):
+        K[l, :, :w.Nk] = dev(wl.K, "bf16")
+        V[l, :, :w.Nk] = dev(wl.V, "bf16")
+        pos[l, :, :w.Nk] = dev(np.broadcast_to(wl.pos_k[None], (hsel, w.Nk, 3)).copy(), None)
+        sco.append(orc.score(wl.Q[:, wl.score_rows], wl.K, wl.scale, share_heads=share))
+        sc[l, :, :w.Nk] = dev(sco[-1].astype(np.float32), None)
+    budgets = budgets_for(w)
+    plan, nk_out = pk.pc_compact_plan(w.segments, budgets)
+    idx = torch.full((3, hsel, nk_out), -1, dtype=torch.int32, device=DEV)
+    ref = []
+    for l in range(3):                                           # one call per layer, out of place
+        Ko = torch.empty((w.Hkv, nk_out, w.D), dtype=K.dtype, device=DEV)
+        Vo, po = torch.empty_like(Ko), torch.empty((hsel, nk_out, 3), dtype=torch.int32, device=DEV)
+        io = torch.empty((hsel, nk_out), dtype=torch.int32, device=DEV)
+        pk.pc_compact(K[l], V[l], pos[l], sc[l], w.segments, budgets, share_heads=share, out=(Ko, Vo, po), idx=io)
+        ref.append((Ko, Vo, po, io))
+    if in_place:
+        segs, nk = pk.pc_compact_batch(K, V, pos, sc, w.segments, budgets, share_heads=share, idx=idx)
+        Kb, Vb, pb = K[:, :, :nk], V[:, :, :nk], pos[:, :, :nk]
+    else:
+        Kb = torch.empty((3, w.Hkv, nk_out, w.D), dtype=K.dtype, device=DEV)
+        Vb, pb = torch.empty_like(Kb), torch.empty((3, hsel, nk_out, 3), dtype=torch.int32, device=DEV)
+        segs, nk = pk.pc_compact_batch(K, V, pos, sc, w.segments, budgets, share_heads=share, out=(Kb, Vb, pb), idx=idx)
+    assert segs == plan and nk == nk_out
+    for l in range(3):
+        Ko, Vo, po, io = ref[l]
+        assert torch.equal(idx[l], io) and torch.equal(Kb[l], Ko) and torch.equal(Vb[l], Vo) and torch.equal(pb[l], po)
+        check_selection(host(idx[l]), sco[l].astype(np.float32).astype(np.float64), w.segments, budgets)
