@@ -168,6 +168,10 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
 #pragma unroll
     for (int s = 0; s < 8; ++s)
       qf[s] = *reinterpret_cast<const bf16x8*>(Qh + static_cast<int64_t>(row) * kD + s * 16 + g * 8);
+    // Make the compiler retire these loads here: otherwise it guards every use of qf inside
+    // the loop with s_waitcnt vmcnt(7..0), which also drains the direct K/V loads in flight.
+#pragma unroll
+    for (int s = 0; s < 8; ++s) asm volatile("" : "+v"(qf[s]));
   }
   f32x16 o[4];
 #pragma unroll
