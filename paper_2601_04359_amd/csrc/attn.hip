@@ -55,20 +55,19 @@ __device__ __forceinline__ void stage_tile(const uint16_t* __restrict__ base_h, 
   }
 }
 
-// One phase of the software pipeline (see the kernel comment): 8 score products and 8
-// value products, alternating, with one element of the probability stage behind each.
+// One phase of the software pipeline (see the kernel comment): 8 score products, then 8
+// value products, with one element of the probability stage behind each.
 __device__ __forceinline__ void pipeline_phase(
     const lds_u8* k_half, const int (&k_off)[8], const lds_u8* v_half, const int (&v_off)[4],
     const bf16x8 (&qf)[8], f32x16& s_nxt, const bf16x8 (&p_mm)[2], f32x16 (&o)[4], const f32x16& s_cur,
     bf16x8 (&p_cur)[2], float& m_ref, float& l_run, float alpha_cur, float& alpha_nxt, float c,
     float rescale_threshold) {
-  // fragment k: even -> K rows, contraction step k/2; odd -> V^T (key step (k/2)/4, block (k/2)%4)
+  // fragment k: 0..7 -> K rows, contraction step k; 8..15 -> V^T (key step (k-8)/4, block (k-8)%4)
   auto frag = [&](int k) -> bf16x8 {
-    const int i = k >> 1;
-    if ((k & 1) == 0) {
-      return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(k_half + k_off[i]);
+    if (k < 8) {
+      return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(k_half + k_off[k]);
     }
-    const int ks = i >> 2, db = i & 3;
+    const int ks = (k - 8) >> 2, db = (k - 8) & 3;
     // keys ks*16 + g*4 + {0..3} and + 8: two transposing reads of 4 keys each
     const lds_u8* p = v_half + v_off[db] + ks * 16 * kRowBytes;
     const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
@@ -90,15 +89,18 @@ __device__ __forceinline__ void pipeline_phase(
 #pragma unroll
   for (int i = 0; i < 16; ++i) zero[i] = 0.f;
   f32x16 s_acc = zero;
-  float psum = 0.f;
+  float psum = 0.f, mx = 0.f;
   float pv[16];
+  // The 8 score products come first, so that the scores are complete while the 8 value
+  // products still issue: their row maximum is folded in behind chunks 10..14 instead of
+  // after the block, where nothing would overlap it.
 #pragma unroll
   for (int k = 0; k < 16; ++k) {
     const bf16x8 f = ring[k % kRing];
-    if ((k & 1) == 0) {
-      s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[k >> 1], k == 0 ? zero : s_acc, 0, 0, 0);
+    if (k < 8) {
+      s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[k], k == 0 ? zero : s_acc, 0, 0, 0);
     } else {
-      const int ks = (k >> 1) >> 2, db = (k >> 1) & 3;
+      const int ks = (k - 8) >> 2, db = (k - 8) & 3;
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, p_mm[ks], o[db], 0, 0, 0);
     }
     if (k + kRing < 16) ring[k % kRing] = frag(k + kRing);
@@ -108,12 +110,11 @@ __device__ __forceinline__ void pipeline_phase(
       p_cur[k >> 3][(k & 7) - 1] = static_cast<__bf16>(pv[k - 1]);
       p_cur[k >> 3][k & 7] = static_cast<__bf16>(pv[k]);
     }
+    if (k == 10) mx = fmaxf(fmaxf(s_acc[0], s_acc[1]), fmaxf(s_acc[2], s_acc[3]));
+    if (k > 10 && k < 15) mx = fmaxf(mx, fmaxf(fmaxf(s_acc[3 * k - 29], s_acc[3 * k - 28]), s_acc[3 * k - 27]));
     __builtin_amdgcn_sched_barrier(0);
   }
-  float mx = s_acc[0];
-#pragma unroll
-  for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s_acc[i]);
-  mx = fmaxf(mx, wave_half_swap(mx)) * c;
+  mx = wave_half_max(mx) * c;
   const float m_new = mx > m_ref + rescale_threshold ? mx : m_ref;
   alpha_nxt = __builtin_amdgcn_exp2f(m_ref - m_new);
   l_run = fmaf(l_run, alpha_cur, psum);
@@ -250,7 +251,7 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     float mx = sA[0];
 #pragma unroll
     for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sA[i]);
-    m_ref = fmaxf(mx, wave_half_swap(mx)) * c;
+    m_ref = wave_half_max(mx) * c;
     if (tail && n == 1) mask_tail(sA, lim_a);
   }
 
@@ -301,7 +302,7 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
         o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pB[ks], o[db], 0, 0, 0);
       }
   }
-  const float l_tot = l_run + wave_half_swap(l_run);
+  const float l_tot = wave_half_sum(l_run);
   const float inv = 1.f / l_tot;
   const int row = row0 + l32;
   if (row < Nq) {

@@ -8,7 +8,29 @@ namespace pc {
 
 typedef __attribute__((address_space(3))) uint8_t lds_u8;
 
-__device__ __forceinline__ float wave_half_swap(float v) { return __shfl_xor(v, 32, 64); }
+// Exchange between lane i and lane i ^ 32 with v_permlane32_swap (one vector instruction, no
+// LDS round trip).  Given the same value in both operands it returns r[0] = the lower half's
+// value in both halves and r[1] = the upper half's value in both halves.
+struct HalfPair {
+  float lo, hi;  // value held by lane (i & 31) and by lane (i & 31) + 32
+};
+__device__ __forceinline__ HalfPair wave_halves(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return {__uint_as_float(r[0]), __uint_as_float(r[1])};
+}
+__device__ __forceinline__ float wave_half_max(float v) {
+  const HalfPair p = wave_halves(v);
+  return fmaxf(p.lo, p.hi);
+}
+__device__ __forceinline__ float wave_half_sum(float v) {
+  const HalfPair p = wave_halves(v);
+  return p.lo + p.hi;
+}
+// the value of the partner lane i ^ 32
+__device__ __forceinline__ float wave_half_swap(float v) {
+  const HalfPair p = wave_halves(v);
+  return (threadIdx.x & 32) ? p.lo : p.hi;
+}
 
 // Tiles are filled by direct global->LDS loads: a wave-wide load writes lane i's 16 bytes at
 // base + 16 i, i.e. four whole 256-byte rows back to back, so rows cannot be padded.  Bank

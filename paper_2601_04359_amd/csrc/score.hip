@@ -359,7 +359,7 @@ __global__ __launch_bounds__(kThreads, 1) void score_colpass_bf16(
   }
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
-    const float v = colsum[b] + wave_half_swap(colsum[b]);
+    const float v = wave_half_sum(colsum[b]);
     const int key = key0 + b * 32 + l32;
     if (g == 0 && key < Nk) out[qsplit * out_stride_split + kvh * out_stride_h + key] = v;
   }
