@@ -7,7 +7,7 @@ heads, D = 128, 4032 tokens per frame, 256 text tokens, 23 past frames):
     pc_budget (gamma 0.85, floor 512) -> pc_compact (select + gather) -> pc_frame_attn.
 Inputs are seeded synthetic tensors already resident in HBM when timing starts.
 Prints ONE JSON line.  `--sweep` adds the per-frame dense-vs-packed table for frames 1..48
-(written to gpurun_out/sweep.json as well).
+(written to sweep.json in the output directory as well).
 """
 from __future__ import annotations
 
@@ -48,13 +48,14 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true", help="per-frame dense vs packed, frames 1..48")
     ap.add_argument("--rollout", action="store_true",
                     help="48-frame rollout of a 28-layer stack (24 query / 8 KV heads), rolling packed cache "
-                         "vs dense cache; per-frame curve written to gpurun_out/rollout.json")
+                         "vs dense cache; per-frame curve written to rollout.json in the output directory")
     ap.add_argument("--rollout-layers", type=int, default=28)
     ap.add_argument("--rollout-frames", type=int, default=48)
     ap.add_argument("--rollout-mode", default="pow", help="pow | norm | half | slide")
     ap.add_argument("--rollout-passes", type=int, default=1,
                     help="attention passes per frame and layer (iterative decoding): with more than one, the "
                          "first pass runs on the un-packed cache and its log-sum-exp feeds the scoring")
+    ap.add_argument("--out-dir", default=os.path.join(ROOT, "gpurun_out"), help="where the per-frame tables go")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-f48", action="store_true", help="skip the frame-48 compaction / dense legs")
     ap.add_argument("--no-dense", action="store_true",
@@ -292,8 +293,8 @@ def main() -> int:
                 sum(r["packed_attn_ms"] + r["score_compact_ms"] for r in last4), 3)
             out["sweep_total_speedup_attn"] = round(sum(r["dense_ms"] for r in table) /
                                                     sum(r["packed_attn_ms"] for r in table), 3)
-            os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-            with open(os.path.join(ROOT, "gpurun_out", "sweep.json"), "w") as fh:
+            os.makedirs(args.out_dir, exist_ok=True)
+            with open(os.path.join(args.out_dir, "sweep.json"), "w") as fh:
                 json.dump(table, fh, indent=0)
         del K48, V48, Q48, Kw, Vw, KL, VL, PL, SL, layers
 
@@ -375,8 +376,8 @@ def main() -> int:
                           "last_frame": curve[-1],
                           "note": "packed_ms covers rope, score, budget, in-place compaction and attention of all "
                                   "layers; dense_ms rope and attention over the full cache"}
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "rollout.json"), "w") as fh:
+        os.makedirs(args.out_dir, exist_ok=True)
+        with open(os.path.join(args.out_dir, "rollout.json"), "w") as fh:
             json.dump(curve, fh, indent=0)
         del packed, dense, Qp, Qd, streams
 
