@@ -152,3 +152,31 @@ def test_masked_budgets_match_the_oracle():
         assert pk.pc_masked_budgets(w.segments, budgets, valid) == orc.masked_budgets(w.segments, budgets, valid)
     with pytest.raises(pk.PackCacheError):
         pk.pc_masked_budgets(w.segments, [-1] * len(w.segments), valid)
+
+
+def test_batched_compaction_and_mask_argument_checks(L):
+    one, two = C.c_void_p(4096), C.c_void_p(8192)
+    seg = (binding.pc_segment * 2)(binding.pc_segment(0, 4, 0, 0), binding.pc_segment(4, 8, 2, 1))
+    bud = (C.c_int32 * 2)(4, 3)
+    ws = L.pc_compact_batch_workspace_bytes(3, 2, 12, 0)
+    assert ws >= L.pc_compact_workspace_bytes(2, 12, 0) > 0
+    assert L.pc_compact_batch_workspace_bytes(0, 2, 12, 0) == 0
+
+    def call(n_layers, kv_l, pos_l, sc_l, in_place=True, hkv=2):
+        Ko = one if in_place else two
+        return L.pc_compact_batch(n_layers, one, one, one, 1, hkv, 128, 12 * 128, kv_l, 36, pos_l, one, 12, sc_l,
+                                  seg, 2, bud, 0, Ko, Ko, Ko, 12 * 128, kv_l, 36, pos_l, None, 0, 0, None, None,
+                                  one, 1 << 24, None)
+    # a layer stride smaller than one layer of K / pos / score
+    assert call(3, 2 * 12 * 128 - 8, 72, 24) == -2
+    assert call(3, 2 * 12 * 128, 71, 24) == -2
+    assert call(3, 2 * 12 * 128, 72, 23) == -2
+    # zero layers; too many (layer, head) pairs for the in-place tickets
+    assert call(0, 0, 0, 0) == -2
+    assert call(129, 2 * 12 * 128, 72, 24) == -4
+    assert b"pairs" in L.pc_last_error_detail()
+    # mask: NULL pointers, short stride; empty input is fine
+    assert L.pc_mask_scores(None, 2, 10, 10, one, None) == -1
+    assert L.pc_mask_scores(one, 2, 10, 9, one, None) == -2
+    assert L.pc_mask_scores(None, 0, 10, 10, None, None) == 0
+    assert L.pc_masked_budgets(seg, 2, bud, None, bud) == -1
