@@ -28,7 +28,7 @@ constexpr int kRowBytes = kD * 2;    // a K or V row in LDS: 256 bytes, unpadded
 constexpr int kTileBytes = kBN * kRowBytes;
 constexpr int kStages = 4;           // LDS slots per operand: tile t lives in slot t % kStages
 constexpr size_t kSmemBytes = 2 * kStages * kTileBytes;
-constexpr float kLazyRescale = 8.f;  // base-2 exponent range allowed before re-referencing
+constexpr float kRescaleTrigger = 1024.f;  // row sum of a half tile that forces a new reference maximum
 constexpr int kRing = 4;
 
 // ---- LDS tile layout ---------------------------------------------------------------------------
@@ -57,11 +57,14 @@ __device__ __forceinline__ void stage_tile(const uint16_t* __restrict__ base_h, 
 
 // One phase of the software pipeline (see the kernel comment): 8 score products, then 8
 // value products, with one element of the probability stage behind each.
+// The probabilities are formed against the reference m_ref as it stands; no maximum is
+// taken on the fast path.  If any row sum of the half tile comes out above kRescaleTrigger
+// (a score outgrew the reference: rare, at most once per 2^10 of growth), the half tile is
+// redone against its exact maximum and O, l are rescaled.
 __device__ __forceinline__ void pipeline_phase(
     const lds_u8* k_half, const int (&k_off)[8], const lds_u8* v_half, const int (&v_off)[4],
     const bf16x8 (&qf)[8], f32x16& s_nxt, const bf16x8 (&p_mm)[2], f32x16 (&o)[4], const f32x16& s_cur,
-    bf16x8 (&p_cur)[2], float& m_ref, float& l_run, float alpha_cur, float& alpha_nxt, float c,
-    float rescale_threshold) {
+    bf16x8 (&p_cur)[2], float& m_ref, float& l_run, float c) {
   // fragment k: 0..7 -> K rows, contraction step k; 8..15 -> V^T (key step (k-8)/4, block (k-8)%4)
   auto frag = [&](int k) -> bf16x8 {
     if (k < 8) {
@@ -89,11 +92,8 @@ __device__ __forceinline__ void pipeline_phase(
 #pragma unroll
   for (int i = 0; i < 16; ++i) zero[i] = 0.f;
   f32x16 s_acc = zero;
-  float psum = 0.f, mx = 0.f;
+  float psum = 0.f;
   float pv[16];
-  // The 8 score products come first, so that the scores are complete while the 8 value
-  // products still issue: their row maximum is folded in behind chunks 10..14 instead of
-  // after the block, where nothing would overlap it.
 #pragma unroll
   for (int k = 0; k < 16; ++k) {
     const bf16x8 f = ring[k % kRing];
@@ -110,20 +110,35 @@ __device__ __forceinline__ void pipeline_phase(
       p_cur[k >> 3][(k & 7) - 1] = static_cast<__bf16>(pv[k - 1]);
       p_cur[k >> 3][k & 7] = static_cast<__bf16>(pv[k]);
     }
-    if (k == 10) mx = fmaxf(fmaxf(s_acc[0], s_acc[1]), fmaxf(s_acc[2], s_acc[3]));
-    if (k > 10 && k < 15) mx = fmaxf(mx, fmaxf(fmaxf(s_acc[3 * k - 29], s_acc[3 * k - 28]), s_acc[3 * k - 27]));
     __builtin_amdgcn_sched_barrier(0);
   }
-  mx = wave_half_max(mx) * c;
-  const float m_new = mx > m_ref + rescale_threshold ? mx : m_ref;
-  alpha_nxt = __builtin_amdgcn_exp2f(m_ref - m_new);
-  l_run = fmaf(l_run, alpha_cur, psum);
-  m_ref = m_new;
-  s_nxt = s_acc;
   // keep the vector results in this basic block (otherwise they sink below the next branch)
 #pragma unroll
   for (int half = 0; half < 2; ++half) asm volatile("" : "+v"(p_cur[half]));
-  asm volatile("" : "+v"(l_run), "+v"(alpha_nxt), "+v"(m_ref));
+  asm volatile("" : "+v"(psum));
+  if (__any(!(psum <= kRescaleTrigger))) {  // also catches inf and NaN
+    float mx = s_cur[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s_cur[i]);
+    const float m_new = fmaxf(m_ref, wave_half_max(mx) * c);
+    const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
+    psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      pv[i] = __builtin_amdgcn_exp2f(fmaf(s_cur[i], c, -m_new));
+      psum += pv[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) p_cur[i >> 3][i & 7] = static_cast<__bf16>(pv[i]);
+    l_run *= alpha;
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+    m_ref = m_new;
+  }
+  l_run += psum;
+  s_nxt = s_acc;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -188,7 +203,7 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
       pA[ks][e] = static_cast<__bf16>(0.f);
       pB[ks][e] = static_cast<__bf16>(0.f);
     }
-  float m_ref = -INFINITY, l_run = 0.f, alpha_a = 1.f, alpha_b = 1.f;
+  float m_ref = -INFINITY, l_run = 0.f;
 
   // per-lane byte offsets inside a half tile
   int k_off[8];  // K fragment of contraction step s: row l32, chunk 2s+g
@@ -231,14 +246,6 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     for (int i = 0; i < 16; ++i)
       if ((i >> 2) * 8 + (i & 3) >= lim) sc[i] = -INFINITY;
   };
-  auto rescale = [&](float alpha) {
-    if (__any(alpha != 1.f)) {
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-    }
-  };
   if (active) {  // S_A of tile 0 and the first reference maximum
     f32x16 zero;
 #pragma unroll
@@ -260,8 +267,7 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     // ---- phase 1: S_B(j), O += V_B(j-1) P_B(j-1)  |  P_A(j), max S_B(j) ----
     if (active) {
       pipeline_phase(smem + k_slot(j) + 32 * kRowBytes, k_off, smem + v_slot(j - 1) + 32 * kRowBytes, v_off, qf, sB, pB,
-                     o, sA, pA, m_ref, l_run, alpha_a, alpha_b, c, kLazyRescale);
-      rescale(alpha_a);
+                     o, sA, pA, m_ref, l_run, c);
       if (last && tail) mask_tail(sB, lim_b);
     }
     // One barrier per tile: every wave is past K(j) and V(j-1), and K(j+1), V(j) (fetched
@@ -271,12 +277,9 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     stage_tile<false>(Kh, (j + kStages) * kBN, Nk, lds0 + k_slot(j), wave, lane);
     stage_tile<true>(Vh, (j + kStages - 1) * kBN, Nk, lds0 + v_slot(j - 1), wave, lane);
     // ---- phase 2: S_A(j+1), O += V_A(j) P_A(j)  |  P_B(j), max S_A(j+1) ----
-    // (after the last tile S_A is formed from a clamped tile: an infinite threshold keeps
-    // its values from moving the reference maximum)
+    // (after the last tile S_A is formed from a clamped tile and never used)
     if (active) {
-      pipeline_phase(smem + k_slot(j + 1), k_off, smem + v_slot(j), v_off, qf, sA, pA, o, sB, pB, m_ref, l_run,
-                     alpha_b, alpha_a, c, last ? INFINITY : kLazyRescale);
-      rescale(alpha_b);
+      pipeline_phase(smem + k_slot(j + 1), k_off, smem + v_slot(j), v_off, qf, sA, pA, o, sB, pB, m_ref, l_run, c);
       if (j + 2 == n && tail) mask_tail(sA, lim_a);
     }
   }

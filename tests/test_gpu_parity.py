@@ -151,6 +151,24 @@ def test_frame_attn_bf16_gqa_groups_and_large_logits():
     _attn_check("bf16", Q, K, V, 128 ** -0.5)
 
 
+@pytest.mark.parametrize("step", [0.05, 0.6, 40.0])
+def test_frame_attn_bf16_reference_maximum_is_refreshed(step):
+    # logits that keep growing along the key axis: the kernel forms probabilities against a
+    # reference maximum it only refreshes when a row sum runs away, so a slow drift (never
+    # refreshed), a steady climb (refreshed every few tiles) and jumps of hundreds of units
+    # (the stale reference overflows to inf first) must all come out right.
+    rng = np.random.default_rng(9)
+    hq, hkv, nq, nk, d = 4, 2, 70, 900, 128
+    Q = rng.standard_normal((hq, nq, d)).astype(np.float32)
+    K = rng.standard_normal((hkv, nk, d)).astype(np.float32) * 0.1
+    V = rng.standard_normal((hkv, nk, d)).astype(np.float32)
+    Q[..., 0] = 8.0
+    ramp = step * (np.arange(nk) // 32)                     # logit contribution grows per half tile
+    K[..., 0] = (ramp / (8.0 * d ** -0.5))[None, :]
+    Q, K, V = synth.to_bf16(Q), synth.to_bf16(K), synth.to_bf16(V)
+    _attn_check("bf16", Q, K, V, d ** -0.5)
+
+
 def test_frame_attn_bf16_closed_forms():
     Q, K, V = _attn_case("bf16", 2, 1, 70, 200, 128, 3)
     Ke = np.repeat(K[:, :1], 200, axis=1)                     # all keys equal -> mean of V
