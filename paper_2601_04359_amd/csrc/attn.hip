@@ -15,6 +15,8 @@
 // fp32 tier (D = 64 or 128): one query row per thread, plain FMA; the correctness tier.
 #include <math.h>
 
+#include <type_traits>
+
 #include "lds_dma.h"
 
 namespace pc {
@@ -262,26 +264,41 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     if (tail && n == 1) mask_tail(sA, lim_a);
   }
 
-  for (int j = 0; j < n; ++j) {
+  // Tile j lives in LDS slot j % 4.  The loop is unrolled four times so that every slot is a
+  // compile-time constant and lands in the offset field of the LDS reads instead of costing a
+  // vector add per fragment address.
+  auto tile_body = [&](int j, auto slot_tag) {
+    constexpr int u = decltype(slot_tag)::value;            // j % kStages
+    constexpr int k_cur = u * kTileBytes, k_nxt = ((u + 1) & 3) * kTileBytes;
+    constexpr int v_prev = (kStages + ((u + 3) & 3)) * kTileBytes, v_cur = (kStages + u) * kTileBytes;
     const bool last = j + 1 == n;
-    // ---- phase 1: S_B(j), O += V_B(j-1) P_B(j-1)  |  P_A(j), max S_B(j) ----
+    // ---- phase 1: S_B(j), O += V_B(j-1) P_B(j-1)  |  P_A(j) ----
     if (active) {
-      pipeline_phase(smem + k_slot(j) + 32 * kRowBytes, k_off, smem + v_slot(j - 1) + 32 * kRowBytes, v_off, qf, sB, pB,
-                     o, sA, pA, m_ref, l_run, c);
+      pipeline_phase(smem + k_cur + 32 * kRowBytes, k_off, smem + v_prev + 32 * kRowBytes, v_off, qf, sB, pB, o, sA,
+                     pA, m_ref, l_run, c);
       if (last && tail) mask_tail(sB, lim_b);
     }
     // One barrier per tile: every wave is past K(j) and V(j-1), and K(j+1), V(j) (fetched
     // kStages - 1 tiles ago) have landed: each wave waited for its own share.
     dma_wait_older();
     __syncthreads();
-    stage_tile<false>(Kh, (j + kStages) * kBN, Nk, lds0 + k_slot(j), wave, lane);
-    stage_tile<true>(Vh, (j + kStages - 1) * kBN, Nk, lds0 + v_slot(j - 1), wave, lane);
-    // ---- phase 2: S_A(j+1), O += V_A(j) P_A(j)  |  P_B(j), max S_A(j+1) ----
+    stage_tile<false>(Kh, (j + kStages) * kBN, Nk, lds0 + k_cur, wave, lane);
+    stage_tile<true>(Vh, (j + kStages - 1) * kBN, Nk, lds0 + v_prev, wave, lane);
+    // ---- phase 2: S_A(j+1), O += V_A(j) P_A(j)  |  P_B(j) ----
     // (after the last tile S_A is formed from a clamped tile and never used)
     if (active) {
-      pipeline_phase(smem + k_slot(j + 1), k_off, smem + v_slot(j), v_off, qf, sA, pA, o, sB, pB, m_ref, l_run, c);
+      pipeline_phase(smem + k_nxt, k_off, smem + v_cur, v_off, qf, sA, pA, o, sB, pB, m_ref, l_run, c);
       if (j + 2 == n && tail) mask_tail(sA, lim_a);
     }
+  };
+  for (int j0 = 0; j0 < n; j0 += kStages) {
+    tile_body(j0, std::integral_constant<int, 0>{});
+    if (j0 + 1 >= n) break;
+    tile_body(j0 + 1, std::integral_constant<int, 1>{});
+    if (j0 + 2 >= n) break;
+    tile_body(j0 + 2, std::integral_constant<int, 2>{});
+    if (j0 + 3 >= n) break;
+    tile_body(j0 + 3, std::integral_constant<int, 3>{});
   }
   if (!active) return;
   // ---- drain: O += V_B(n-1) P_B(n-1) ----
