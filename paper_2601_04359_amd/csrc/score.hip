@@ -21,6 +21,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "lds_dma.h"
 
@@ -89,19 +90,37 @@ __device__ __forceinline__ void stream_phase(const lds_u8* half, const int (&a_o
 struct RowState {
   float m[2], l[2];
 };
+constexpr float kRowTrigger = 1024.f;  // phase sum that forces a new reference maximum
 
-__device__ __forceinline__ void row_epilogue(int i, const f32x16 (&s)[2], RowState& st, float c) {
+// Element pair i of the previous half tile: p = exp2(c s - m) against the reference as it
+// stands, summed into the phase's partial sums.  No maximum is taken here.
+__device__ __forceinline__ void row_epilogue(int i, const f32x16 (&s)[2], const RowState& st, float (&psum)[2],
+                                             float c) {
   const int b = i >> 3, e = (i & 7) * 2;
-  if ((i & 7) == 0) {
-    float mx = fmaxf(s[b][0], s[b][1]);
+  psum[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e], c, -st.m[b]));
+  psum[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e + 1], c, -st.m[b]));
+}
+// After the phase: add the partial sums; if one ran away (a score outgrew the reference, or
+// the reference is still the initial sentinel) redo that half tile against its exact maximum.
+__device__ __forceinline__ void row_commit(const f32x16 (&s)[2], RowState& st, float (&psum)[2], float c) {
 #pragma unroll
-    for (int k = 2; k < 16; k += 2) mx = fmaxf(mx, fmaxf(s[b][k], s[b][k + 1]));
-    const float m_new = fmaxf(st.m[b], mx * c);
-    st.l[b] *= __builtin_amdgcn_exp2f(st.m[b] - m_new);
-    st.m[b] = m_new;
+  for (int b = 0; b < 2; ++b) {
+    asm volatile("" : "+v"(psum[b]));
+    if (__any(!(psum[b] <= kRowTrigger))) {
+      float mx = fmaxf(s[b][0], s[b][1]);
+#pragma unroll
+      for (int k = 2; k < 16; k += 2) mx = fmaxf(mx, fmaxf(s[b][k], s[b][k + 1]));
+      const float m_new = fmaxf(st.m[b], mx * c);
+      float sum = 0.f;
+#pragma unroll
+      for (int k = 0; k < 16; ++k) sum += __builtin_amdgcn_exp2f(fmaf(s[b][k], c, -m_new));
+      st.l[b] = st.l[b] * __builtin_amdgcn_exp2f(st.m[b] - m_new) + sum;
+      st.m[b] = m_new;
+    } else {
+      st.l[b] += psum[b];
+    }
+    psum[b] = 0.f;
   }
-  st.l[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e], c, -st.m[b]));
-  st.l[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e + 1], c, -st.m[b]));
 }
 
 __device__ __forceinline__ void mask_keys(f32x16 (&s)[2], int k0, int Nk, int g) {
@@ -174,26 +193,42 @@ __global__ __launch_bounds__(kThreads, 1) void score_rowpass_bf16(
   st.l[0] = st.l[1] = 0.f;
   f32x16 sA[2], sB[2];
 
+  float psum[2] = {0.f, 0.f};
   stage(0);
   stage(1);
   stage(2);
   asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
   __syncthreads();
   stream_phase(slot(0), a_off, qf, sA, [](int) {});
-  for (int j = 0; j < n; ++j) {
+  // Tile j lives in LDS slot j % 4; the loop is unrolled over the slots so that their bases are
+  // immediates of the LDS reads.
+  auto tile_body = [&](int j, auto slot_tag) {
+    constexpr int u = decltype(slot_tag)::value;
     const bool tail = (t_begin + j + 1) * kTileRows > Nk;  // only ever the last tile
     dma_wait_all_but_newest();
     __syncthreads();  // tile j+1 has landed everywhere; slot of tile j-1 is free
     stage(j + 3);
     if (tail) mask_keys(sA, (t_begin + j) * kTileRows, Nk, g);
-    stream_phase(slot(j) + 32 * kRowBytes, a_off, qf, sB, [&](int i) { row_epilogue(i, sA, st, c); });
+    stream_phase(smem + u * kTileBytes + 32 * kRowBytes, a_off, qf, sB,
+                 [&](int i) { row_epilogue(i, sA, st, psum, c); });
+    row_commit(sA, st, psum, c);
     if (tail) mask_keys(sB, (t_begin + j) * kTileRows + 32, Nk, g);
     if (j + 1 < n) {
-      stream_phase(slot(j + 1), a_off, qf, sA, [&](int i) { row_epilogue(i, sB, st, c); });
+      stream_phase(smem + ((u + 1) & 3) * kTileBytes, a_off, qf, sA, [&](int i) { row_epilogue(i, sB, st, psum, c); });
     } else {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) row_epilogue(i, sB, st, c);
+      for (int i = 0; i < 16; ++i) row_epilogue(i, sB, st, psum, c);
     }
+    row_commit(sB, st, psum, c);
+  };
+  for (int j0 = 0; j0 < n; j0 += kStages) {
+    tile_body(j0, std::integral_constant<int, 0>{});
+    if (j0 + 1 >= n) break;
+    tile_body(j0 + 1, std::integral_constant<int, 1>{});
+    if (j0 + 2 >= n) break;
+    tile_body(j0 + 2, std::integral_constant<int, 2>{});
+    if (j0 + 3 >= n) break;
+    tile_body(j0 + 3, std::integral_constant<int, 3>{});
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no direct load may outlive the work-group
 
@@ -340,20 +375,31 @@ __global__ __launch_bounds__(kThreads, 1) void score_colpass_bf16(
     asm volatile("s_waitcnt vmcnt(4)" ::: "memory");  // at least the first tile's pieces
     __syncthreads();
     stream_phase(slot(0), a_off, kf, sA, [](int) {});
-    for (int j = 0; j < n; ++j) {
+    auto tile_body = [&](int j, auto slot_tag) {  // slot j % 4 as a compile-time constant, as in pass 1
+      constexpr int u = decltype(slot_tag)::value;
       dma_wait_all_but_newest();
       __syncthreads();  // tile j+1 has landed everywhere; slot of tile j-1 is free
       stage(j + 3, rows);
       src_rows(j + 4, rows);
-      load_lq(j, 0, lq);
-      stream_phase(slot(j) + 32 * kRowBytes, a_off, kf, sB, [&](int i) { col_epilogue(i, sA, lq, colsum, c); });
-      load_lq(j, 1, lq);
+      load_lq(u, 0, lq);
+      stream_phase(smem + u * kTileBytes + 32 * kRowBytes, a_off, kf, sB,
+                   [&](int i) { col_epilogue(i, sA, lq, colsum, c); });
+      load_lq(u, 1, lq);
       if (j + 1 < n) {
-        stream_phase(slot(j + 1), a_off, kf, sA, [&](int i) { col_epilogue(i, sB, lq, colsum, c); });
+        stream_phase(smem + ((u + 1) & 3) * kTileBytes, a_off, kf, sA, [&](int i) { col_epilogue(i, sB, lq, colsum, c); });
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) col_epilogue(i, sB, lq, colsum, c);
       }
+    };
+    for (int j0 = 0; j0 < n; j0 += kStages) {
+      tile_body(j0, std::integral_constant<int, 0>{});
+      if (j0 + 1 >= n) break;
+      tile_body(j0 + 1, std::integral_constant<int, 1>{});
+      if (j0 + 2 >= n) break;
+      tile_body(j0 + 2, std::integral_constant<int, 2>{});
+      if (j0 + 3 >= n) break;
+      tile_body(j0 + 3, std::integral_constant<int, 3>{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // no direct load may outlive the work-group
   }

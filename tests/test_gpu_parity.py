@@ -232,6 +232,26 @@ def test_score_bf16_ragged(n_qs, nk):
     _score_check(w, Qs, K)
 
 
+@pytest.mark.parametrize("step", [0.05, 0.6, 40.0])
+def test_score_bf16_row_reference_is_refreshed(step):
+    # the row pass sums exp2 against a standing reference and redoes a half tile only when a
+    # partial sum runs away: logits drifting, climbing and jumping along the key axis
+    rng = np.random.default_rng(4)
+    hq, hkv, n_qs, nk, d = 4, 2, 90, 1100, 128
+    w = synth.midsize()
+    Qs = rng.standard_normal((hq, n_qs, d)).astype(np.float32)
+    K = rng.standard_normal((hkv, nk, d)).astype(np.float32) * 0.1
+    Qs[..., 0] = 8.0
+    K[..., 0] = (step * (np.arange(nk) // 32) / (8.0 * d ** -0.5))[None, :]
+    Qs, K = synth.to_bf16(Qs), synth.to_bf16(K)
+    got = host(pk.pc_score(dev(Qs, "bf16"), dev(K, "bf16"), nk, d ** -0.5)).astype(np.float64)
+    want = orc.score(Qs, K, d ** -0.5)
+    # fp32 exponents: a logit of magnitude L carries an absolute rounding error of about
+    # L * 2^-23 in base-2 units twice over (the product c*s and the subtraction of the LSE)
+    rel = max(2e-5, 4 * step * (nk // 32) * 1.4427 * 2.0 ** -23)
+    assert np.all(np.abs(got - want) <= 2e-7 + rel * want), (np.abs(got - want) / (want + 1e-30)).max()
+
+
 def test_score_with_supplied_lse_matches_internal_pass():
     w = synth.midsize()
     Qs = w.Q[:, w.score_rows]
