@@ -6,7 +6,7 @@
  * Sec. 3.4), every past frame keeps a token budget that decays with its temporal
  * distance (Eq. 4-8), the tokens kept inside a frame are the attention-relevant ones,
  * dropped tokens are physically removed (Fig. 5(b)), and every kept token retains its
- * original (t, h, w) rotary position (Sec. 3.4, Eq. 9).  The current frame's queries then
+ * original (t, h, w) rotary position (Sec. 3.4).  The current frame's queries then
  * attend to the compacted cache (Eq. 2).
  *
  * Conventions shared by every call
@@ -61,7 +61,8 @@ typedef struct pc_segment {
 
 #define PC_MAX_SEGMENTS 120
 #define PC_MAX_SELECT_LEN 4096 /* longest FRAME segment the register-resident select handles
-                                  in one wave; longer segments take a slower generic path */
+                                  (one work-group per segment); longer segments take a slower
+                                  generic path */
 
 const char* pc_strerror(int status);
 const char* pc_last_error_detail(void);
