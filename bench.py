@@ -27,6 +27,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # default workload only and are reported, not re-measured, here.
 TRAFFIC_ATTN_F24_PACKED_BYTES = int((67164.4 * 1.9998 + 16128.0) * 1024)
 TRAFFIC_COMPACT_F48_G085_BYTES = int((41670.6 * 1.9998 + 76945.4) * 1024)   # per layer, in place
+TRAFFIC_COMPACT_BATCH_F48_G085_BYTES = int((1164894.8 * 1.9998 + 2154470.5) * 1024 / 28)   # per layer, one call
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
@@ -254,7 +255,9 @@ def main() -> int:
         out["roofline_compact_batched"] = {"bound": "hbm", "kernel": "pc_compact_batch: one select_block_kernel + one "
                                            "gather_kernel launch for 28 layers, in place, gamma 0.85",
                                            "achieved": comp_b["0.85"]["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                           "frac": comp_b["0.85"]["frac_hbm"], "traffic": None}
+                                           "frac": comp_b["0.85"]["frac_hbm"],
+                                           "traffic": TRAFFIC_COMPACT_BATCH_F48_G085_BYTES,
+                                           "traffic_unit": "bytes per layer"}
         out["roofline_compact"] = {"bound": "hbm", "kernel": "pc_compact = select_block_kernel + gather_kernel, in place, gamma 0.85, 28 layers",
                                    "achieved": comp["0.85"]["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                    "frac": comp["0.85"]["frac_hbm"],
