@@ -205,7 +205,9 @@ def main() -> int:
         SL = sc48[None].expand(n_layers, -1, -1).contiguous()
         layers = [(KL[l], VL[l], PL[l], torch.empty_like(ws_c48)) for l in range(n_layers)]
         ws_b48 = torch.empty(pk.pc_compact_batch_workspace_bytes(n_layers, Hkv, Nk48), dtype=torch.uint8, device=dev)
-        comp, comp_b = {}, {}
+        comp, comp_b, comp_p = {}, {}, {}
+        side_stream = torch.cuda.Stream()
+        ev_sel = [torch.cuda.Event() for _ in range(n_layers)]
         for gamma in (0.7, 0.85, 0.95):
             b48 = pk.segment_budgets(w48.segments, pk.pc_budget(pk.PC_BUDGET_POW, w48.n_frame, 47, gamma, 512))
             _, nk48p = pk.pc_compact_plan(w48.segments, b48)
@@ -227,6 +229,32 @@ def main() -> int:
             gb = gather_bytes(kept, Hkv, D) / 1e9
             comp[str(gamma)] = {"kept_past_rows": kept, "ms_per_layer": round(ms, 4),
                                 "GBps": round(gb / (ms * 1e-3), 1), "frac_hbm": round(gb / (ms * 1e-3) / PEAK_HBM_GBS, 4)}
+            # the same per-layer calls, the select half of every layer on a side stream (it reads
+            # only the scores), the gather half behind it on the main stream
+            main, side = torch.cuda.current_stream(), side_stream
+            sel = [pk.pc_compact_prepared(Kl, Vl, pl, sc48, w48.segments, b48, wl, phases=pk.PC_COMPACT_SELECT,
+                                          stream=side) for (Kl, Vl, pl, wl) in layers]
+            gat = [pk.pc_compact_prepared(Kl, Vl, pl, sc48, w48.segments, b48, wl, phases=pk.PC_COMPACT_GATHER,
+                                          stream=main) for (Kl, Vl, pl, wl) in layers]
+            tp = []
+            for rep in range(4):
+                for (Kl, Vl, pl, _) in layers:
+                    Kl.copy_(K48), Vl.copy_(V48), pl.copy_(pos48)
+                torch.cuda.synchronize()
+                a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(main)
+                side.wait_event(a)
+                for l in range(n_layers):
+                    sel[l]()
+                    ev_sel[l].record(side)
+                    main.wait_event(ev_sel[l])
+                    gat[l]()
+                e.record(main)
+                torch.cuda.synchronize()
+                tp.append(a.elapsed_time(e) / n_layers)
+            msp = float(np.mean(tp[1:]))
+            comp_p[str(gamma)] = {"ms_per_layer": round(msp, 4), "GBps": round(gb / (msp * 1e-3), 1),
+                                  "frac_hbm": round(gb / (msp * 1e-3) / PEAK_HBM_GBS, 4)}
             tb = []
             for rep in range(4):                                        # the whole stack in one call
                 KL.copy_(K48[None].expand_as(KL)), VL.copy_(V48[None].expand_as(VL)), PL.copy_(pos48[None].expand_as(PL))
@@ -252,6 +280,7 @@ def main() -> int:
         score48_ms = timed(lambda: pk.pc_score(Q48, K48, Nk48, w48.scale, score=sc48, ws=ws_s48, q_rows=rows48), 3)
         out["compaction_f48_in_place"] = comp
         out["compaction_f48_in_place_batched"] = comp_b
+        out["compaction_f48_in_place_two_streams"] = comp_p
         out["roofline_compact_batched"] = {"bound": "hbm", "kernel": "pc_compact_batch: one select_block_kernel + one "
                                            "gather_kernel launch for 28 layers, in place, gamma 0.85",
                                            "achieved": comp_b["0.85"]["GBps"], "peak": PEAK_HBM_GBS, "unit": "GB/s",

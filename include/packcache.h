@@ -216,6 +216,26 @@ int pc_compact_batch(int n_layers, void* K, void* V, int32_t* pos, int dtype, in
                      int32_t* Nk_out, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * pc_compact_batch_phase -- the two halves of pc_compact_batch as separate calls, so that a
+ * caller can overlap them on two streams: the SELECT of the next layer (reads only scores;
+ * writes the kept-row indices and resets the in-place bookkeeping in the workspace) runs
+ * while the GATHER of the current layer moves rows.  phases = PC_COMPACT_SELECT, then
+ * PC_COMPACT_GATHER with the SAME arguments and workspace (the caller orders the two with an
+ * event when they are on different streams), or both bits at once (= pc_compact_batch).
+ * Every argument is checked in both calls; SELECT does not touch K, V or pos.
+ */
+enum { PC_COMPACT_SELECT = 1, PC_COMPACT_GATHER = 2 };
+int pc_compact_batch_phase(int phases, int n_layers, void* K, void* V, int32_t* pos, int dtype, int Hkv,
+                           int D, int64_t kv_stride_h, int64_t kv_stride_l, int64_t pos_stride_h,
+                           int64_t pos_stride_l, const float* score, int64_t score_stride_h,
+                           int64_t score_stride_l, const pc_segment* seg_in, int n_seg,
+                           const int32_t* budget, int share_heads, void* K_out, void* V_out,
+                           int32_t* pos_out, int64_t kv_out_stride_h, int64_t kv_out_stride_l,
+                           int64_t pos_out_stride_h, int64_t pos_out_stride_l, int32_t* idx_out,
+                           int64_t idx_stride_h, int64_t idx_stride_l, pc_segment* seg_out,
+                           int32_t* Nk_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Cache mask (Sec. 3.1: a binary mask says which generated tokens are visible to later
  * frames; Sec. 3.4: PackCache removes the masked positions instead of storing them).
  * One flag per cached token, the same for every head: valid[j] != 0 keeps token j a

@@ -13,7 +13,7 @@ __all__ = [
     "PC_F32", "PC_BF16", "PC_SEG_TEXT", "PC_SEG_COND", "PC_SEG_FRAME", "PC_SEG_SELF",
     "PC_BUDGET_POW", "PC_BUDGET_NORM", "PC_BUDGET_HALF", "PC_BUDGET_SLIDE", "PC_MAX_SEGMENTS",
     "PackCacheError", "lib", "lib_path", "pc_version", "pc_strerror", "pc_budget", "pc_rope3d", "pc_rebase",
-    "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact", "pc_compact_batch", "pc_compact_batch_workspace_bytes", "pc_masked_budgets", "pc_mask_scores",
+    "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact", "pc_compact_batch", "pc_compact_batch_workspace_bytes", "PC_COMPACT_SELECT", "PC_COMPACT_GATHER", "pc_masked_budgets", "pc_mask_scores",
     "pc_compact_workspace_bytes", "pc_compact_prepared", "pc_frame_attn", "pc_frame_attn_workspace_bytes",
     "segment_budgets",
 ]
@@ -21,6 +21,7 @@ __all__ = [
 PC_F32, PC_BF16 = 0, 1
 PC_SEG_TEXT, PC_SEG_COND, PC_SEG_FRAME, PC_SEG_SELF = 0, 1, 2, 3
 PC_BUDGET_POW, PC_BUDGET_NORM, PC_BUDGET_HALF, PC_BUDGET_SLIDE = 0, 1, 2, 3
+PC_COMPACT_SELECT, PC_COMPACT_GATHER = 1, 2
 PC_MAX_SEGMENTS = 120
 
 _LIB = None
@@ -70,6 +71,7 @@ def lib() -> C.CDLL:
         L.pc_compact_batch.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, i64, i64, i64, i64, vp, i64,
                                        i64, segp, C.c_int, i32p, C.c_int, vp, vp, vp, i64, i64, i64, i64, vp, i64,
                                        i64, segp, i32p, vp, sz, vp]
+        L.pc_compact_batch_phase.argtypes = [C.c_int] + list(L.pc_compact_batch.argtypes)
         L.pc_masked_budgets.argtypes = [segp, C.c_int, i32p, vp, i32p]
         L.pc_mask_scores.argtypes = [vp, C.c_int, C.c_int, i64, vp, vp]
         L.pc_compact_plan.argtypes = [segp, C.c_int, i32p, segp, i32p]
@@ -278,19 +280,23 @@ def pc_compact_batch(K, V, pos, score, segments, budgets, share_heads: bool = Fa
     return [(s.start, s.len, s.kind, s.frame) for s in seg_out[:n]], nk.value
 
 
-def pc_compact_prepared(K, V, pos, score, segments, budgets, ws, share_heads: bool = False, out=None, idx=None):
+def pc_compact_prepared(K, V, pos, score, segments, budgets, ws, share_heads: bool = False, out=None, idx=None,
+                        phases: int = 3, stream=None):
     """Marshal the arguments of pc_compact once; returns a callable that only makes the C
-    call (for launch loops where Python-side marshalling would dominate)."""
+    call (for launch loops where Python-side marshalling would dominate).  phases: 1 = the
+    select half, 2 = the gather half, 3 = both; stream: a torch stream (default: the
+    current one at preparation time)."""
     Hkv, _, D = K.shape
     n = len(segments)
     seg_in = _seg_array(segments)
     b = (C.c_int32 * max(n, 1))(*[int(v) for v in budgets])
     Ko, Vo, po = (K, V, pos) if out is None else out
-    fn = lib().pc_compact
-    args = (K.data_ptr(), V.data_ptr(), pos.data_ptr(), _dtype_code(K), Hkv, D, K.stride(0), pos.stride(0),
-            score.data_ptr(), score.stride(0), seg_in, n, b, int(share_heads), Ko.data_ptr(), Vo.data_ptr(),
-            po.data_ptr(), Ko.stride(0), po.stride(0), _ptr(idx), 0 if idx is None else idx.stride(0), None, None,
-            ws.data_ptr(), ws.numel(), _stream())
+    fn = lib().pc_compact_batch_phase
+    args = (int(phases), 1, K.data_ptr(), V.data_ptr(), pos.data_ptr(), _dtype_code(K), Hkv, D, K.stride(0), 0,
+            pos.stride(0), 0, score.data_ptr(), score.stride(0), 0, seg_in, n, b, int(share_heads), Ko.data_ptr(),
+            Vo.data_ptr(), po.data_ptr(), Ko.stride(0), 0, po.stride(0), 0, _ptr(idx),
+            0 if idx is None else idx.stride(0), 0, None, None, ws.data_ptr(), ws.numel(),
+            _stream() if stream is None else stream.cuda_stream)
 
     def call():
         _check(fn(*args))

@@ -479,6 +479,24 @@ extern "C" int pc_compact_batch(int n_layers, void* K, void* V, int32_t* pos, in
                                 int64_t pos_out_stride_h, int64_t pos_out_stride_l, int32_t* idx_out,
                                 int64_t idx_stride_h, int64_t idx_stride_l, pc_segment* seg_out,
                                 int32_t* Nk_out, void* ws, size_t ws_bytes, void* stream) {
+  return pc_compact_batch_phase(PC_COMPACT_SELECT | PC_COMPACT_GATHER, n_layers, K, V, pos, dtype, Hkv, D,
+                                kv_stride_h, kv_stride_l, pos_stride_h, pos_stride_l, score, score_stride_h,
+                                score_stride_l, seg_in, n_seg, budget, share_heads, K_out, V_out, pos_out,
+                                kv_out_stride_h, kv_out_stride_l, pos_out_stride_h, pos_out_stride_l, idx_out,
+                                idx_stride_h, idx_stride_l, seg_out, Nk_out, ws, ws_bytes, stream);
+}
+
+extern "C" int pc_compact_batch_phase(int phases, int n_layers, void* K, void* V, int32_t* pos, int dtype, int Hkv,
+                                      int D, int64_t kv_stride_h, int64_t kv_stride_l, int64_t pos_stride_h,
+                                      int64_t pos_stride_l, const float* score, int64_t score_stride_h,
+                                      int64_t score_stride_l, const pc_segment* seg_in, int n_seg,
+                                      const int32_t* budget, int share_heads, void* K_out, void* V_out,
+                                      int32_t* pos_out, int64_t kv_out_stride_h, int64_t kv_out_stride_l,
+                                      int64_t pos_out_stride_h, int64_t pos_out_stride_l, int32_t* idx_out,
+                                      int64_t idx_stride_h, int64_t idx_stride_l, pc_segment* seg_out,
+                                      int32_t* Nk_out, void* ws, size_t ws_bytes, void* stream) {
+  PC_REQUIRE(phases >= 1 && phases <= (PC_COMPACT_SELECT | PC_COMPACT_GATHER), PC_ERR_SHAPE,
+             "pc_compact: phases=%d", phases);
   PC_REQUIRE(dtype == PC_F32 || dtype == PC_BF16, PC_ERR_DTYPE, "pc_compact: dtype %d", dtype);
   PC_REQUIRE(Hkv > 0 && D > 0 && n_layers >= 1, PC_ERR_SHAPE, "pc_compact: layers=%d Hkv=%d D=%d", n_layers, Hkv, D);
   PC_REQUIRE(n_seg >= 0 && n_seg <= PC_MAX_SEGMENTS, PC_ERR_SHAPE,
@@ -562,7 +580,9 @@ extern "C" int pc_compact_batch(int n_layers, void* K, void* V, int32_t* pos, in
   // the select kernel also clears the in-place gather's counters and flags (contiguous in ws)
   int32_t* clear = in_place ? reinterpret_cast<int32_t*>(sync) : nullptr;
   const int n_clear = in_place ? static_cast<int>((lay.total - lay.sync_off) / sizeof(int32_t)) : 0;
-  if (max_prune_len <= 256)
+  if (!(phases & PC_COMPACT_SELECT)) {
+    // indices and cleared counters come from an earlier SELECT call with the same arguments
+  } else if (max_prune_len <= 256)
     select_block_kernel<1><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear, hsel,
                                                    score_stride_l, idx_stride_layer);
   else if (max_prune_len <= 1024)
@@ -581,6 +601,7 @@ extern "C" int pc_compact_batch(int n_layers, void* K, void* V, int32_t* pos, in
     }
   }
   PC_CHECK_LAUNCH("pc_compact select");
+  if (!(phases & PC_COMPACT_GATHER)) return PC_OK;
 
   const int cpr = row_bytes / 16;
   constexpr int kRowsInPlace = 64;

@@ -520,3 +520,40 @@ def test_compact_batch_equals_layer_by_layer_and_the_oracle(in_place, share):
         Ko, Vo, po, io = ref[l]
         assert torch.equal(idx[l], io) and torch.equal(Kb[l], Ko) and torch.equal(Vb[l], Vo) and torch.equal(pb[l], po)
         check_selection(host(idx[l]), sco[l].astype(np.float32).astype(np.float64), w.segments, budgets)
+
+
+@pytest.mark.parametrize("in_place", [False, True])
+def test_select_and_gather_as_two_calls_on_two_streams(in_place):
+    # the select half on a side stream, the gather half on the main stream behind an event:
+    # same result, bit for bit, as the single call
+    w = synth.midsize()
+    sco = orc.score(w.Q[:, w.score_rows], w.K, w.scale)
+    budgets = budgets_for(w)
+    ref = _compact_run(w, sco, budgets, in_place)
+    K, V = dev(w.K, "bf16"), dev(w.V, "bf16")
+    pos = dev(np.broadcast_to(w.pos_k[None], (w.Hkv, w.Nk, 3)).copy(), None)
+    sc = dev(sco.astype(np.float32), None)
+    plan, nk = pk.pc_compact_plan(w.segments, budgets)
+    idx = torch.full((w.Hkv, nk), -1, dtype=torch.int32, device=DEV)
+    ws = torch.empty(pk.pc_compact_workspace_bytes(w.Hkv, w.Nk), dtype=torch.uint8, device=DEV)
+    if in_place:
+        out, (Ko, Vo, po) = None, (K, V, pos)
+    else:
+        Ko = torch.empty((w.Hkv, nk, w.D), dtype=K.dtype, device=DEV)
+        Vo, po = torch.empty_like(Ko), torch.empty((w.Hkv, nk, 3), dtype=torch.int32, device=DEV)
+        out = (Ko, Vo, po)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    select = pk.pc_compact_prepared(K, V, pos, sc, w.segments, budgets, ws, out=out, idx=idx,
+                                    phases=pk.PC_COMPACT_SELECT, stream=side)
+    gather = pk.pc_compact_prepared(K, V, pos, sc, w.segments, budgets, ws, out=out, idx=idx,
+                                    phases=pk.PC_COMPACT_GATHER)
+    select()
+    done = torch.cuda.Event()
+    done.record(side)
+    torch.cuda.current_stream().wait_event(done)
+    gather()
+    torch.cuda.synchronize()
+    assert np.array_equal(host(idx), ref[3])
+    assert np.array_equal(host(Ko[:, :nk]), ref[0]) and np.array_equal(host(Vo[:, :nk]), ref[1])
+    assert np.array_equal(host(po[:, :nk]), ref[2])
