@@ -181,6 +181,13 @@ int pc_compact_plan(const pc_segment* seg_in, int n_seg, const int32_t* budget,
  *   seg_out   host [n_seg] or NULL, Nk_out host or NULL: as from pc_compact_plan.
  * Hsel = Hkv (every KV head keeps its own rows; counts are equal so tensors stay
  * rectangular) or 1 when share_heads != 0 (one selection for all heads).
+ * In place, work-groups take their chunk of packed rows by ticket, load it, and wait (a
+ * bounded spin) until every earlier chunk that still has to read the destination rows has
+ * loaded them.  The tickets, flags and an abort word live in the workspace, so two calls that
+ * run concurrently must not share a workspace, and a workspace must not be reused by another
+ * stream before the call that uses it has finished.  The spin bound cannot be hit while the
+ * workspace is used by one call at a time; if it is, the waiting work-groups give up, the
+ * result of that call is undefined and nothing hangs.
  * Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE (n_seg > PC_MAX_SEGMENTS, strides,
  * table), PC_ERR_BUDGET, PC_ERR_WORKSPACE, PC_ERR_HIP.
  */

@@ -441,14 +441,9 @@ extern "C" int pc_frame_attn(const void* Q, const void* K, const void* V, int dt
                          reinterpret_cast<uintptr_t>(V) | reinterpret_cast<uintptr_t>(O);
     PC_REQUIRE(al % 16 == 0 && q_stride_h % 8 == 0 && kv_stride_h % 8 == 0 && o_stride_h % 8 == 0,
                PC_ERR_SHAPE, "pc_frame_attn: bf16 tensors and head strides must be 16-byte aligned");
-    static bool attr_set = false;
-    if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         static_cast<int>(kSmemBytes));
-      if (e != hipSuccess) PC_FAIL(PC_ERR_HIP, "pc_frame_attn: LDS attribute: %s", hipGetErrorString(e));
-      attr_set = true;
-    }
+    static std::atomic<uint64_t> lds_ok{0};
+    if (int rc = allow_dynamic_lds(reinterpret_cast<const void*>(attn_bf16_kernel), kSmemBytes, lds_ok, "pc_frame_attn"))
+      return rc;
     const int n_tiles_q = ceil_div(Nq, kBM);
     const float c = scale * 1.4426950408889634f;
     attn_bf16_kernel<<<dim3(n_tiles_q * Hq), kPPThreads, kSmemBytes, s>>>(

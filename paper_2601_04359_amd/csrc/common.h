@@ -2,6 +2,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stdarg.h>
 #include <stdint.h>
 #include <stdio.h>
@@ -30,6 +32,19 @@ void set_detail(const char* fmt, ...);  // thread-local message for pc_last_erro
     hipError_t e_ = hipGetLastError();                                              \
     if (e_ != hipSuccess) PC_FAIL(PC_ERR_HIP, "%s: %s", what, hipGetErrorString(e_)); \
   } while (0)
+
+// Raises a kernel's dynamic-LDS limit once per device; `done` is the caller's per-kernel
+// bit mask of devices already served.  Safe to call from several host threads.
+inline int allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done, const char* who) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+  const uint64_t bit = 1ull << dev;
+  if (done.load(std::memory_order_acquire) & bit) return PC_OK;
+  const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+  if (e != hipSuccess) PC_FAIL(PC_ERR_HIP, "%s: LDS attribute: %s", who, hipGetErrorString(e));
+  done.fetch_or(bit, std::memory_order_release);
+  return PC_OK;
+}
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

@@ -558,14 +558,6 @@ int choose_splits(int base, int n_tiles, int max_splits) {
   return best;
 }
 
-template <class Kernel>
-int allow_lds(Kernel kernel, size_t bytes) {
-  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
-  if (e != hipSuccess) PC_FAIL(PC_ERR_HIP, "pc_score: LDS attribute: %s", hipGetErrorString(e));
-  return PC_OK;
-}
-
 }  // namespace
 }  // namespace pc
 
@@ -610,12 +602,11 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
     const uintptr_t al = reinterpret_cast<uintptr_t>(Qs) | reinterpret_cast<uintptr_t>(K);
     PC_REQUIRE(al % 16 == 0 && q_stride_h % 8 == 0 && k_stride_h % 8 == 0, PC_ERR_SHAPE,
                "pc_score: bf16 tensors and head strides must be 16-byte aligned");
-    static bool attr_set = false;
-    if (!attr_set) {
-      if (int rc = allow_lds(score_rowpass_bf16, kRowSmem)) return rc;
-      if (int rc = allow_lds(score_colpass_bf16, kColSmem)) return rc;
-      attr_set = true;
-    }
+    static std::atomic<uint64_t> row_ok{0}, col_ok{0};
+    if (int rc = allow_dynamic_lds(reinterpret_cast<const void*>(score_rowpass_bf16), kRowSmem, row_ok, "pc_score"))
+      return rc;
+    if (int rc = allow_dynamic_lds(reinterpret_cast<const void*>(score_colpass_bf16), kColSmem, col_ok, "pc_score"))
+      return rc;
     const float c = scale * 1.4426950408889634f;
     const int n_pad = padded_rows(n_qs);
     if (lse == nullptr) {
