@@ -37,7 +37,7 @@ class RollingLayer:
     def __init__(self, Hq: int, Hkv: int, D: int, capacity: int, n_frame: int, scale: float,
                  mode: str = "pow", gamma: float = 0.85, b_min: int = 512, budget_tokens: int | None = None,
                  n_score: int = 512, sections=(32, 48, 48), base: float = 10000.0, dtype=None, device="cuda:0",
-                 slide_t_scale: int | None = None):
+                 slide_t_scale: int | None = None, share_heads: bool = False):
         import torch
         if mode not in MODES:
             raise ValueError(f"mode {mode!r} not in {sorted(MODES)}")
@@ -47,24 +47,28 @@ class RollingLayer:
         self.budget_tokens = n_frame if budget_tokens is None else budget_tokens
         self.sections, self.base = tuple(sections), base
         dtype = torch.bfloat16 if dtype is None else dtype
+        # share_heads: one selection for all KV heads (the paper's per-token cache mask) instead
+        # of one per KV head; positions and scores then have a single head
+        self.share_heads = share_heads
+        hsel = 1 if share_heads else Hkv
         self.K = torch.empty((Hkv, capacity, D), dtype=dtype, device=device)
         self.V = torch.empty_like(self.K)
-        self.pos = torch.empty((Hkv, capacity, 3), dtype=torch.int32, device=device)
+        self.pos = torch.empty((hsel, capacity, 3), dtype=torch.int32, device=device)
         self.segments: list[tuple[int, int, int, int]] = []
         self.nk = 0
         self.slide_t_scale, self.shift = slide_t_scale, 0
         n_rows = min(n_score, n_frame)
         self.q_rows = ((torch.arange(n_rows, dtype=torch.int64) * n_frame) // n_rows).to(torch.int32).to(device)
         if mode != "dense":   # the full-cache baseline neither scores nor compacts
-            self.score = torch.empty((Hkv, capacity), dtype=torch.float32, device=device)
-            self._ws_score = torch.empty(pk.pc_score_workspace_bytes(Hq, Hkv, n_rows, capacity), dtype=torch.uint8,
-                                         device=device)
-            self._ws_compact = torch.empty(pk.pc_compact_workspace_bytes(Hkv, capacity), dtype=torch.uint8,
-                                           device=device)
+            self.score = torch.empty((hsel, capacity), dtype=torch.float32, device=device)
+            self._ws_score = torch.empty(pk.pc_score_workspace_bytes(Hq, Hkv, n_rows, capacity, share_heads),
+                                         dtype=torch.uint8, device=device)
+            self._ws_compact = torch.empty(pk.pc_compact_workspace_bytes(Hkv, capacity, share_heads),
+                                           dtype=torch.uint8, device=device)
 
     # ---- insertion: the producer writes straight into the cache, no copy ----------------------
     def reserve(self, n: int):
-        """Views of the next n free rows: (K rows, V rows, pos rows [Hkv][n][3])."""
+        """Views of the next n free rows: (K rows, V rows, pos rows [Hsel][n][3])."""
         if self.nk + n > self.capacity:
             raise ValueError(f"cache capacity {self.capacity} < {self.nk} + {n}")
         a = self.nk
@@ -114,10 +118,10 @@ class RollingLayer:
         stands, e.g. from attend(): scoring then needs one QK^T pass instead of two."""
         if self.mode == "dense":
             return
-        pk.pc_score(Q, self.K, self.nk, self.scale, lse=lse, score=self.score, ws=self._ws_score,
-                    q_rows=self.q_rows)
+        pk.pc_score(Q, self.K, self.nk, self.scale, lse=lse, score=self.score, share_heads=self.share_heads,
+                    ws=self._ws_score, q_rows=self.q_rows)
         self.segments, self.nk = pk.pc_compact(self.K, self.V, self.pos, self.score, self.segments,
-                                               self.budgets(), ws=self._ws_compact)
+                                               self.budgets(), share_heads=self.share_heads, ws=self._ws_compact)
 
     def attend(self, Q, O=None, lse=None):
         """The (rotated) queries Q over the cache as it stands -> O (and the log-sum-exp)."""

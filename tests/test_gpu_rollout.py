@@ -39,22 +39,24 @@ def _insert(layer, K, V, p, kind, frame):
     k, v, pp = layer.reserve(n)
     k.copy_(dev(K.astype(np.float32), "bf16"))
     v.copy_(dev(V, "bf16"))
-    pp.copy_(dev(np.broadcast_to(p[None], (layer.Hkv, n, 3)).copy(), None))
+    pp.copy_(dev(np.broadcast_to(p[None], (pp.shape[0], n, 3)).copy(), None))
     layer.commit(n, kind, frame)
 
 
-@pytest.mark.parametrize("mode,gamma,b_min", [("pow", 0.85, 32), ("pow", 0.6, 16), ("norm", 0.7, 20),
-                                              ("half", 1.0, 30), ("half", 1.0, 60), ("slide", 1.0, 0),
-                                              ("dense", 1.0, 0)])
-def test_rolling_layer_matches_oracle(mode, gamma, b_min):
+@pytest.mark.parametrize("mode,gamma,b_min,share", [
+    ("pow", 0.85, 32, False), ("pow", 0.6, 16, False), ("norm", 0.7, 20, False), ("half", 1.0, 30, False),
+    ("half", 1.0, 60, False), ("slide", 1.0, 0, False), ("dense", 1.0, 0, False), ("pow", 0.85, 32, True),
+    ("half", 1.0, 60, True)])
+def test_rolling_layer_matches_oracle(mode, gamma, b_min, share):
     case = synth.rolling_case(seed=11, n_steps=6)
     aK, frames, queries = _rotated(case)
     want = orc.rolling_rollout(aK, case.anchor_V, case.anchor_pos, case.anchor_segments, frames, queries,
-                               case.scale, _budget_fn(mode, case, gamma, b_min), score_rows=case.score_rows)
+                               case.scale, _budget_fn(mode, case, gamma, b_min), score_rows=case.score_rows,
+                               share_heads=share)
     n = case.n_frame
     layer = RollingLayer(case.Hq, case.Hkv, case.D, case.anchor_K.shape[1] + len(frames) * n, n, case.scale,
                          mode=mode, gamma=gamma, b_min=b_min, n_score=case.score_rows.size,
-                         sections=case.sections, base=case.base, device=DEV)
+                         sections=case.sections, base=case.base, device=DEV, share_heads=share)
     assert np.array_equal(host(layer.q_rows), case.score_rows)
     for (start, length, kind, frame) in case.anchor_segments:
         _insert(layer, aK[:, start:start + length], case.anchor_V[:, start:start + length],
