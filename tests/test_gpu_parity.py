@@ -557,3 +557,42 @@ def test_select_and_gather_as_two_calls_on_two_streams(in_place):
     assert np.array_equal(host(idx), ref[3])
     assert np.array_equal(host(Ko[:, :nk]), ref[0]) and np.array_equal(host(Vo[:, :nk]), ref[1])
     assert np.array_equal(host(po[:, :nk]), ref[2])
+
+
+def test_random_shapes_attention_score_compaction():
+    # a seeded walk over ragged shapes and head groupings: every call against the oracle
+    rng = np.random.default_rng(2024)
+    for it in range(24):
+        hkv = int(rng.choice([1, 2, 3]))
+        hq = hkv * int(rng.choice([1, 2, 4]))
+        nq, nk = int(rng.integers(1, 400)), int(rng.integers(1, 1500))
+        Q = synth.to_bf16(rng.standard_normal((hq, nq, 128)).astype(np.float32))
+        K = synth.to_bf16(rng.standard_normal((hkv, nk, 128)).astype(np.float32))
+        V = synth.to_bf16(rng.standard_normal((hkv, nk, 128)).astype(np.float32))
+        scale = 128 ** -0.5
+        _attn_check("bf16", Q, K, V, scale)
+        n_qs = int(rng.integers(1, min(nq, 200) + 1))
+        rows = np.sort(rng.choice(nq, size=n_qs, replace=False)).astype(np.int32)
+        sc = pk.pc_score(dev(Q, "bf16"), dev(K, "bf16"), nk, scale, q_rows=dev(rows, None))
+        want = orc.score(Q[:, rows], K, scale)
+        assert np.all(np.abs(host(sc) - want) <= 2e-7 + 2e-5 * want), (it, hq, hkv, nq, nk)
+        # a random segment table over the keys: [text | frames...], random budgets
+        n_text = int(rng.integers(0, min(nk, 40) + 1))
+        n_cuts = min(int(rng.integers(0, 6)), nk - n_text)
+        cuts = np.sort(rng.choice(np.arange(n_text, nk + 1), size=n_cuts, replace=False))
+        bounds = [n_text] + [int(c) for c in cuts] + [nk]
+        segs = [(0, n_text, pk.PC_SEG_TEXT, -1)] + [(a, b - a, pk.PC_SEG_FRAME, f + 1)
+                                                    for f, (a, b) in enumerate(zip(bounds[:-1], bounds[1:]))]
+        budgets = [n_text] + [int(rng.integers(0, s[1] + 2)) for s in segs[1:]]
+        pos = np.broadcast_to(np.arange(nk, dtype=np.int32)[None, :, None], (hkv, nk, 3)).copy()
+        Kd, Vd, pd = dev(K, "bf16"), dev(V, "bf16"), dev(pos, None)
+        plan, nk_out = pk.pc_compact_plan(segs, budgets)
+        idx = torch.full((hkv, max(nk_out, 1)), -1, dtype=torch.int32, device=DEV)
+        segs_out, nk2 = pk.pc_compact(Kd, Vd, pd, sc, segs, budgets, idx=idx)
+        assert segs_out == plan == orc.packed_segments(segs, budgets) and nk2 == nk_out
+        if nk_out:
+            ig = host(idx)[:, :nk_out]
+            check_selection(ig, host(sc).astype(np.float64), segs, budgets, band=0.0)   # exact on the device's own scores
+            for h in range(hkv):
+                assert np.array_equal(host(Kd[h, :nk_out]), K[h][ig[h]]) and np.array_equal(host(Vd[h, :nk_out]), V[h][ig[h]])
+                assert np.array_equal(host(pd[h, :nk_out]), pos[h][ig[h]])
