@@ -1,16 +1,20 @@
 // pc_compact: per-frame top-k selection and physical compaction (Sec. 3.4, Fig. 5(b)).
 //
-//   select   one wavefront per (selection head, segment).  Scores of a past-frame segment
-//            sit in registers (up to 64 per lane); a bit-by-bit radix select on the
-//            order-preserving integer image of the fp32 score finds the k-th largest value
-//            with wave ballots only (no LDS, no atomics); equal scores are taken lowest
-//            index first; the kept indices come out ascending.
-//   gather   HBM-bound.  A work-group owns 32 consecutive packed rows of one KV head:
-//            it loads its K, V and position rows (16 bytes per lane), then stores them.
-//            In place, a work-group may only store once every work-group whose SOURCE rows
-//            lie in its destination range has finished loading.  Work-groups take their
-//            chunk from an atomic ticket, so a chunk only ever waits on chunks with a lower
-//            ticket, which are already running and whose loads wait on nothing.
+//   select   one work-group per (layer, selection head, segment).  The scores of a past-frame
+//            segment sit in registers as order-preserving integers; the k-th largest is found
+//            eight bits at a time with an LDS histogram (the bits all keys share are skipped,
+//            and the search stops as soon as the k-th key is alone in its bin); equal scores
+//            are taken lowest index first; the kept indices come out ascending.  Segments
+//            longer than PC_MAX_SELECT_LEN take a one-wave, bit-by-bit variant that re-reads
+//            the scores.
+//   gather   HBM-bound.  A work-group owns 32 (in place: 64) consecutive packed rows of one
+//            KV head: it loads its K, V and position rows (16 bytes per lane), then stores
+//            them.  In place, a work-group may only store once every work-group whose SOURCE
+//            rows lie in its destination range has finished loading.  Work-groups take their
+//            chunk from an atomic ticket per (layer, head), so a chunk only ever waits on
+//            chunks with a lower ticket, which are already running and whose loads wait on
+//            nothing.
+//   A stack of layers is handled by the same two launches (layer strides).
 #include <limits.h>
 
 #include <algorithm>
