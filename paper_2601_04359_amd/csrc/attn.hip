@@ -2,16 +2,16 @@
 //
 // bf16 tier (D = 128): flash-style kernel on the gfx950 32x32x16 bf16 MFMA.
 //   * Scores are formed transposed, S^T = K Q^T: in the MFMA result layout a lane then
-//     holds ONE query column and 16 keys per 32-key block.  The running max / sum of a
-//     query are per-lane scalars (one cross-lane exchange per half tile), and the
-//     probabilities are already laid out as the B operand of the second product
-//     O^T += V^T P^T, so P never goes through LDS.
+//     holds ONE query column and 16 keys per 32-key block.  The reference maximum and the
+//     running sum of a query are per-lane scalars, and the probabilities are already laid
+//     out as the B operand of the second product O^T += V^T P^T, so P never goes through LDS.
 //   * K and V tiles are fetched straight from global memory into LDS (no register
 //     staging), four tiles deep; V stays row-major in LDS and is transposed by the LDS
 //     transposing read on its way into the MFMA A operand.
 //   * Softmax in fp32 with base-2 exponentials, interleaved instruction by instruction with
-//     the products of the neighbouring half tiles; accumulators are rescaled only when a
-//     row maximum outgrows the reference by 2^8.
+//     the products of the neighbouring half tiles.  No row maximum is taken on the fast path:
+//     probabilities are formed against the standing reference, and a half tile is redone
+//     (and the accumulators rescaled) only when one of its row sums runs away.
 // fp32 tier (D = 64 or 128): one query row per thread, plain FMA; the correctness tier.
 #include <math.h>
 
@@ -149,7 +149,7 @@ __device__ __forceinline__ void pipeline_phase(
 // On this chip matrix and vector instructions overlap only inside one wave's instruction
 // stream, so every wave interleaves, in one basic block per phase,
 //     matrix:  S_nxt^T = K_half Q^T (8 products)  and  O^T += V_half^T P_mm^T (8 products)
-//     vector:  P_cur = exp2(c S_cur - m_ref) and its row sum; then the row maximum of S_nxt
+//     vector:  P_cur = exp2(c S_cur - m_ref), its bf16 packing and its row sum
 // where cur is the half tile scored one phase earlier and mm the one before that:
 //     phase 1 of tile j:  S_B(j), O += V_B(j-1) P_B(j-1)  |  P_A(j)
 //     phase 2 of tile j:  S_A(j+1), O += V_A(j) P_A(j)    |  P_B(j)

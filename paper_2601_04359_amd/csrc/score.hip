@@ -4,7 +4,8 @@
 // Two passes over Q K^T, both on the 32x32x16 bf16 MFMA and both free of atomics so the
 // result is bit-reproducible:
 //   1. row pass:    log-sum-exp of every scoring query over all keys (keys split over
-//                   work-groups, partial (max, sum) pairs merged in a fixed order);
+//                   work-groups, partial (reference, sum) pairs merged in a fixed order; the
+//                   reference is refreshed only when a partial sum runs away);
 //   2. column pass: p = exp2(c*s - lse2) with the FINAL normaliser, un-rounded, in fp32,
 //                   summed down the query axis (queries split over work-groups, partial
 //                   sums added in a fixed order).
