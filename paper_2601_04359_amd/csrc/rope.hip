@@ -44,34 +44,42 @@ __global__ __launch_bounds__(kThreads) void rope3d_kernel(T* __restrict__ x, int
   __syncthreads();
 
   constexpr int kElems = 16 / sizeof(T);  // elements per 16-byte chunk
+  constexpr int kHeadsInFlight = 4;       // loads of several heads are issued before any is used
   const int chunks_per_row = D / kElems;
   const int total = kTokPerBlock * chunks_per_row;
-  for (int h = 0; h < H; ++h) {
-    T* xh = x + h * stride_h;
-    for (int e = threadIdx.x; e < total; e += kThreads) {
-      const int t = e / chunks_per_row, c = e % chunks_per_row;
-      const int tok = tok0 + t;
-      if (tok >= n) continue;
-      u32x4* p = reinterpret_cast<u32x4*>(xh + static_cast<int64_t>(tok) * D + c * kElems);
-      u32x4 raw = *p;
-      if constexpr (sizeof(T) == 2) {
+  for (int e = threadIdx.x; e < total; e += kThreads) {
+    const int t = e / chunks_per_row, c = e % chunks_per_row;
+    const int tok = tok0 + t;
+    if (tok >= n) continue;
+    T* x0 = x + static_cast<int64_t>(tok) * D + c * kElems;
+    for (int h0 = blockIdx.y * kHeadsInFlight; h0 < H; h0 += gridDim.y * kHeadsInFlight) {
+      u32x4 raw[kHeadsInFlight];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const float2 r = cs[t][c * 4 + k];
-          const float x0 = bf16_to_f32(static_cast<uint16_t>(raw[k] & 0xFFFFu));
-          const float x1 = bf16_to_f32(static_cast<uint16_t>(raw[k] >> 16));
-          raw[k] = pack_bf16x2(x0 * r.x - x1 * r.y, x0 * r.y + x1 * r.x);
-        }
-      } else {
+      for (int i = 0; i < kHeadsInFlight; ++i)
+        if (h0 + i < H) raw[i] = *reinterpret_cast<const u32x4*>(x0 + (h0 + i) * stride_h);
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {
-          const float2 r = cs[t][c * 2 + k];
-          const float x0 = __uint_as_float(raw[2 * k]), x1 = __uint_as_float(raw[2 * k + 1]);
-          raw[2 * k] = __float_as_uint(x0 * r.x - x1 * r.y);
-          raw[2 * k + 1] = __float_as_uint(x0 * r.y + x1 * r.x);
+      for (int i = 0; i < kHeadsInFlight; ++i) {
+        if constexpr (sizeof(T) == 2) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const float2 r = cs[t][c * 4 + k];
+            const float a0 = bf16_to_f32(static_cast<uint16_t>(raw[i][k] & 0xFFFFu));
+            const float a1 = bf16_to_f32(static_cast<uint16_t>(raw[i][k] >> 16));
+            raw[i][k] = pack_bf16x2(a0 * r.x - a1 * r.y, a0 * r.y + a1 * r.x);
+          }
+        } else {
+#pragma unroll
+          for (int k = 0; k < 2; ++k) {
+            const float2 r = cs[t][c * 2 + k];
+            const float a0 = __uint_as_float(raw[i][2 * k]), a1 = __uint_as_float(raw[i][2 * k + 1]);
+            raw[i][2 * k] = __float_as_uint(a0 * r.x - a1 * r.y);
+            raw[i][2 * k + 1] = __float_as_uint(a0 * r.y + a1 * r.x);
+          }
         }
       }
-      *p = raw;
+#pragma unroll
+      for (int i = 0; i < kHeadsInFlight; ++i)
+        if (h0 + i < H) *reinterpret_cast<u32x4*>(x0 + (h0 + i) * stride_h) = raw[i];
     }
   }
 }
@@ -156,7 +164,9 @@ extern "C" int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride
     fr.inv_freq[p] = 0.0;
     fr.axis[p] = 0;
   }
-  const dim3 grid(ceil_div(n, kTokPerBlock));
+  // heads are dealt to grid.y in groups of four when there are many: more work-groups in flight
+  // for the price of recomputing the (shared) sines and cosines
+  const dim3 grid(ceil_div(n, kTokPerBlock), H >= 8 ? 2 : 1);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == PC_BF16)
     rope3d_kernel<uint16_t><<<grid, kThreads, 0, s>>>(static_cast<uint16_t*>(x), H, n, D, stride_h, pos, fr);
