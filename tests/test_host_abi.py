@@ -180,3 +180,10 @@ def test_batched_compaction_and_mask_argument_checks(L):
     assert L.pc_mask_scores(one, 2, 10, 9, one, None) == -2
     assert L.pc_mask_scores(None, 0, 10, 10, None, None) == 0
     assert L.pc_masked_budgets(seg, 2, bud, None, bud) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode != 0 and "ONE GPU" in p.stderr and p.stdout.strip() == ""
