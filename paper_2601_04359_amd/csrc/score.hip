@@ -256,13 +256,16 @@ __global__ void score_merge_rows(const float2* __restrict__ part, float* __restr
     return;
   }
   const int64_t n_rows = static_cast<int64_t>(Hq) * n_qs, at = static_cast<int64_t>(h) * n_qs + row;
+  float2 p[kMaxSplits];  // all partials first: the loads are independent and overlap
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s) p[s] = s < n_splits ? part[s * n_rows + at] : make_float2(kNoMax, 0.f);
   float m = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) m = fmaxf(m, part[s * n_rows + at].x);
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s) m = fmaxf(m, p[s].x);
   float l = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const float2 p = part[s * n_rows + at];
-    if (p.y > 0.f) l += p.y * exp2f(p.x - m);
-  }
+#pragma unroll
+  for (int s = 0; s < kMaxSplits; ++s)
+    if (p[s].y > 0.f) l += p[s].y * exp2f(p[s].x - m);
   lse2[r] = m + log2f(l);
 }
 
