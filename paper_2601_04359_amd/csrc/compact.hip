@@ -336,8 +336,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
       const int src = min(max(idx_h[row], 0), Nk_in - 1);  // a valid table never needs the clamp
       if (!kInPlace || src != row) {
         const int64_t so = in_base + static_cast<int64_t>(src) * cpr + ch;
-        kval[it] = K[so];
-        vval[it] = V[so];
+        kval[it] = __builtin_nontemporal_load(&K[so]);
+        vval[it] = __builtin_nontemporal_load(&V[so]);
         dst_off[it] = out_base + static_cast<int64_t>(row) * cpr + ch;
       }
     }
@@ -412,8 +412,8 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
 #pragma unroll
   for (int it = 0; it < kPasses; ++it) {
     if (dst_off[it] >= 0) {
-      Ko[dst_off[it]] = kval[it];
-      Vo[dst_off[it]] = vval[it];
+      __builtin_nontemporal_store(kval[it], &Ko[dst_off[it]]);
+      __builtin_nontemporal_store(vval[it], &Vo[dst_off[it]]);
     }
   }
   if (pdst >= 0) pos_o[pdst] = pval;
