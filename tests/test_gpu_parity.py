@@ -596,3 +596,52 @@ def test_random_shapes_attention_score_compaction():
             for h in range(hkv):
                 assert np.array_equal(host(Kd[h, :nk_out]), K[h][ig[h]]) and np.array_equal(host(Vd[h, :nk_out]), V[h][ig[h]])
                 assert np.array_equal(host(pd[h, :nk_out]), pos[h][ig[h]])
+
+
+def test_random_segment_tables_batched_in_and_out_of_place():
+    # random cache sizes (up to 40k rows), segment tables (also segments longer than the
+    # register-resident select handles), budgets, layer counts, tie-heavy scores, both selection
+    # granularities: kept sets against a full sort, moved rows bit for bit, in place == out of place
+    for it in range(12):
+        rng = np.random.default_rng(7000 + it)
+        hkv, L = int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 3]))
+        nk = int(rng.integers(1, 40000))
+        n_text = int(rng.integers(0, min(nk, 300) + 1))
+        n_cuts = min(int(rng.integers(0, 40)), nk - n_text)
+        cuts = np.sort(rng.choice(np.arange(n_text, nk + 1), size=n_cuts, replace=False))
+        bounds = [n_text] + [int(c) for c in cuts] + [nk]
+        segs = [(0, n_text, pk.PC_SEG_TEXT, -1)] + [(a, b - a, pk.PC_SEG_FRAME, f + 1)
+                                                    for f, (a, b) in enumerate(zip(bounds[:-1], bounds[1:]))]
+        frac = float(rng.choice([0.05, 0.3, 0.7, 0.95, 1.0]))
+        budgets = [n_text] + [int(min(s[1], max(0, round(s[1] * frac) + int(rng.integers(-2, 3))))) for s in segs[1:]]
+        share = bool(rng.integers(0, 2))
+        hsel = 1 if share else hkv
+        g = torch.Generator(device=DEV)
+        g.manual_seed(7000 + it)
+        K = torch.randn((L, hkv, nk, 128), device=DEV, generator=g).to(torch.bfloat16)
+        V = torch.randn((L, hkv, nk, 128), device=DEV, generator=g).to(torch.bfloat16)
+        pos = torch.randint(0, 1000, (L, hsel, nk, 3), device=DEV, generator=g, dtype=torch.int32)
+        sc = torch.rand((L, hsel, nk), device=DEV, generator=g)
+        if it % 2:
+            sc = (sc * 8).floor() / 8                             # many equal scores
+        plan, nko = pk.pc_compact_plan(segs, budgets)
+        if nko == 0:
+            continue
+        Ko = torch.empty((L, hkv, nko, 128), dtype=K.dtype, device=DEV)
+        Vo = torch.empty_like(Ko)
+        po = torch.empty((L, hsel, nko, 3), dtype=torch.int32, device=DEV)
+        io = torch.empty((L, hsel, nko), dtype=torch.int32, device=DEV)
+        pk.pc_compact_batch(K, V, pos, sc, segs, budgets, share_heads=share, out=(Ko, Vo, po), idx=io)
+        sch, ioh = host(sc).astype(np.float64), host(io)
+        for l in range(L):
+            check_selection(ioh[l], sch[l], segs, budgets, band=0.0)
+            for h in range(hkv):
+                sel = io[l, 0 if share else h].long()
+                assert torch.equal(Ko[l, h], K[l, h].index_select(0, sel)), (it, l, h)
+                assert torch.equal(Vo[l, h], V[l, h].index_select(0, sel)), (it, l, h)
+            for h in range(hsel):
+                assert torch.equal(po[l, h], pos[l, h].index_select(0, io[l, h].long()))
+        i2 = torch.empty_like(io)
+        pk.pc_compact_batch(K, V, pos, sc, segs, budgets, share_heads=share, idx=i2)
+        assert torch.equal(i2, io) and torch.equal(K[:, :, :nko], Ko) and torch.equal(V[:, :, :nko], Vo)
+        assert torch.equal(pos[:, :, :nko], po), it
