@@ -160,7 +160,8 @@ __device__ __forceinline__ void pipeline_phase(
 __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     uint16_t* __restrict__ O, float* __restrict__ lse, int rep, int Nq, int Nk, int64_t q_stride_h,
-    int64_t kv_stride_h, int64_t o_stride_h, float c, int n_tiles_q) {
+    int64_t kv_stride_h, int64_t o_stride_h, float c, int n_tiles_q, int n_splits, float* __restrict__ part_o,
+    float2* __restrict__ part_ml) {
   extern __shared__ __align__(16) uint8_t smem_raw[];
   lds_u8* smem = (lds_u8*)smem_raw;
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(smem));
@@ -171,7 +172,10 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, g = lane >> 5;
   const int L = xcd_contiguous_index(blockIdx.x, gridDim.x);
-  const int h = L / n_tiles_q, tile = L % n_tiles_q;
+  // logical order: key split slowest, then head, then row tile
+  const int Hq_tiles = static_cast<int>(gridDim.x) / n_splits;
+  const int split = L / Hq_tiles;
+  const int h = (L % Hq_tiles) / n_tiles_q, tile = L % n_tiles_q;
   const int kvh = h / rep;
   const int row0 = tile * kBM + wave * 32;
   const bool active = row0 < Nq;  // wave-uniform
@@ -222,9 +226,14 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     }
   }
 
-  const int n = (Nk + kBN - 1) / kBN;
-  const bool tail = (Nk % kBN) != 0;
-  const int lim_a = Nk - (n - 1) * kBN - g * 4;  // last tile: first invalid key offset, half A
+  // this work-group's share of the key tiles: [t0, t0 + n) of n_all (the host leaves no share empty)
+  const int n_all = (Nk + kBN - 1) / kBN;
+  const int per = (n_all + n_splits - 1) / n_splits;
+  const int t0 = split * per;
+  const int n = min(per, n_all - t0);
+  const int key0 = t0 * kBN;
+  const bool tail = (Nk % kBN) != 0 && t0 + n == n_all;   // the ragged last tile is in this share
+  const int lim_a = Nk - (n_all - 1) * kBN - g * 4;  // last tile: first invalid key offset, half A
   const int lim_b = lim_a - 32;
 
   // the V slot of "tile -1" is read once against zero probabilities: clear it
@@ -233,13 +242,13 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
   // Prologue, in order of need: K(0), V(0), K(1), then K(2), V(1), K(3), V(2).  Tiles past the
   // end of the cache are fetched too (clamped rows, never read) so that every staging point
   // issues the same number of loads and the in-flight count can be waited on.
-  stage_tile<false>(Kh, 0, Nk, lds0 + k_slot(0), wave, lane);
-  stage_tile<true>(Vh, 0, Nk, lds0 + v_slot(0), wave, lane);
-  stage_tile<false>(Kh, kBN, Nk, lds0 + k_slot(1), wave, lane);
-  stage_tile<false>(Kh, 2 * kBN, Nk, lds0 + k_slot(2), wave, lane);
-  stage_tile<true>(Vh, kBN, Nk, lds0 + v_slot(1), wave, lane);
-  stage_tile<false>(Kh, 3 * kBN, Nk, lds0 + k_slot(3), wave, lane);
-  stage_tile<true>(Vh, 2 * kBN, Nk, lds0 + v_slot(2), wave, lane);
+  stage_tile<false>(Kh, key0, Nk, lds0 + k_slot(0), wave, lane);
+  stage_tile<true>(Vh, key0, Nk, lds0 + v_slot(0), wave, lane);
+  stage_tile<false>(Kh, key0 + kBN, Nk, lds0 + k_slot(1), wave, lane);
+  stage_tile<false>(Kh, key0 + 2 * kBN, Nk, lds0 + k_slot(2), wave, lane);
+  stage_tile<true>(Vh, key0 + kBN, Nk, lds0 + v_slot(1), wave, lane);
+  stage_tile<false>(Kh, key0 + 3 * kBN, Nk, lds0 + k_slot(3), wave, lane);
+  stage_tile<true>(Vh, key0 + 2 * kBN, Nk, lds0 + v_slot(2), wave, lane);
   dma_wait_older();
   __syncthreads();
 
@@ -282,8 +291,8 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     // kStages - 1 tiles ago) have landed: each wave waited for its own share.
     dma_wait_older();
     __syncthreads();
-    stage_tile<false>(Kh, (j + kStages) * kBN, Nk, lds0 + k_cur, wave, lane);
-    stage_tile<true>(Vh, (j + kStages - 1) * kBN, Nk, lds0 + v_prev, wave, lane);
+    stage_tile<false>(Kh, key0 + (j + kStages) * kBN, Nk, lds0 + k_cur, wave, lane);
+    stage_tile<true>(Vh, key0 + (j + kStages - 1) * kBN, Nk, lds0 + v_prev, wave, lane);
     // ---- phase 2: S_A(j+1), O += V_A(j) P_A(j)  |  P_B(j) ----
     // (after the last tile S_A is formed from a clamped tile and never used)
     if (active) {
@@ -323,8 +332,25 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
       }
   }
   const float l_tot = wave_half_sum(l_run);
-  const float inv = 1.f / l_tot;
   const int row = row0 + l32;
+  if (part_o != nullptr) {  // one of several key shares: un-normalised O, reference and sum for the merge
+    if (row < Nq) {
+      const int64_t at = (static_cast<int64_t>(split) * gridDim.x / n_splits / n_tiles_q + h) * Nq + row;
+      float* prow = part_o + at * kD;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = o[db][a * 4 + e];
+          *reinterpret_cast<f32x4*>(prow + db * 32 + a * 8 + g * 4) = v;
+        }
+      if (g == 0) part_ml[at] = make_float2(m_ref, l_tot);
+    }
+    return;
+  }
+  const float inv = 1.f / l_tot;
   if (row < Nq) {
     uint16_t* orow = O + h * o_stride_h + static_cast<int64_t>(row) * kD;
 #pragma unroll
@@ -339,6 +365,62 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     if (lse != nullptr && g == 0)
       lse[static_cast<int64_t>(h) * Nq + row] = (m_ref + log2f(l_tot)) * 0.6931471805599453f;
   }
+}
+
+// Merge of the key shares: O = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s with M = max_s m_s.
+// A thread owns four dims of one row.
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o,
+                                                         const float2* __restrict__ part_ml,
+                                                         uint16_t* __restrict__ O, float* __restrict__ lse,
+                                                         int Hq, int Nq, int64_t o_stride_h, int n_splits) {
+  const int64_t r = static_cast<int64_t>(blockIdx.x) * 8 + (threadIdx.x >> 5);
+  const int c = threadIdx.x & 31;
+  const int64_t n_rows = static_cast<int64_t>(Hq) * Nq;
+  if (r >= n_rows) return;
+  float M = -INFINITY;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, part_ml[s * n_rows + r].x);
+  float l = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < n_splits; ++s) {
+    const float2 ml = part_ml[s * n_rows + r];
+    const float w = __builtin_amdgcn_exp2f(ml.x - M);
+    l += w * ml.y;
+    const f32x4 v = *reinterpret_cast<const f32x4*>(part_o + (s * n_rows + r) * kD + c * 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[e] += w * v[e];
+  }
+  const float inv = 1.f / l;
+  const int h = static_cast<int>(r / Nq), row = static_cast<int>(r % Nq);
+  u32x2 out;
+  out[0] = pack_bf16x2(acc[0] * inv, acc[1] * inv);
+  out[1] = pack_bf16x2(acc[2] * inv, acc[3] * inv);
+  *reinterpret_cast<u32x2*>(O + h * o_stride_h + static_cast<int64_t>(row) * kD + c * 4) = out;
+  if (lse != nullptr && c == 0) lse[r] = (M + log2f(l)) * 0.6931471805599453f;
+}
+
+// How many shares to cut the keys into: none unless it fills the 256 compute units in whole
+// rounds noticeably better (e.g. 24 heads x 16 row tiles = 384 work-groups: 1.5 rounds -> 3 rounds
+// of half the length), never so fine that a share's prologue shows.
+int choose_key_splits(int base_blocks, int n_tiles) {
+  int best = 1;
+  double best_score = 0.0;
+  for (int s = 1; s <= 4; ++s) {
+    const int per = ceil_div(n_tiles, s);
+    if (s > 1 && (per < 16 || ceil_div(n_tiles, per) != s)) continue;
+    const int blocks = base_blocks * s, rounds = ceil_div(blocks, 256);
+    const double score = static_cast<double>(blocks) / (rounds * 256.0) * per / (per + 2.0) * (s == 1 ? 1.08 : 1.0);
+    if (score > best_score) {
+      best_score = score;
+      best = s;
+    }
+  }
+  return best;
+}
+
+size_t attn_partial_bytes(int Hq, int Nq, int n_splits) {
+  return n_splits <= 1 ? 0
+                       : align_up(static_cast<size_t>(n_splits) * Hq * Nq * kD * sizeof(float), 256) +
+                             align_up(static_cast<size_t>(n_splits) * Hq * Nq * sizeof(float2), 256);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -418,12 +500,15 @@ __global__ __launch_bounds__(kF32Threads) void attn_f32_kernel(
 
 using namespace pc;
 
-extern "C" size_t pc_frame_attn_workspace_bytes(int, int, int, int) { return 0; }
+extern "C" size_t pc_frame_attn_workspace_bytes(int Hq, int Nq, int Nk, int D) {
+  if (D != kD || Hq <= 0 || Nq <= 0 || Nk <= 0) return 0;   // only the bf16 kernel splits the keys
+  return attn_partial_bytes(Hq, Nq, choose_key_splits(Hq * ceil_div(Nq, kBM), ceil_div(Nk, kBN)));
+}
 
 extern "C" int pc_frame_attn(const void* Q, const void* K, const void* V, int dtype, int Hq,
                              int Hkv, int Nq, int Nk, int D, int64_t q_stride_h,
                              int64_t kv_stride_h, int64_t o_stride_h, float scale, void* O,
-                             float* lse, void* /*ws*/, size_t /*ws_bytes*/, void* stream) {
+                             float* lse, void* ws, size_t ws_bytes, void* stream) {
   PC_REQUIRE(dtype == PC_F32 || dtype == PC_BF16, PC_ERR_DTYPE, "pc_frame_attn: dtype %d", dtype);
   PC_REQUIRE(Hq > 0 && Hkv > 0 && Hq % Hkv == 0, PC_ERR_SHAPE,
              "pc_frame_attn: Hq=%d must be a positive multiple of Hkv=%d", Hq, Hkv);
@@ -446,10 +531,27 @@ extern "C" int pc_frame_attn(const void* Q, const void* K, const void* V, int dt
       return rc;
     const int n_tiles_q = ceil_div(Nq, kBM);
     const float c = scale * 1.4426950408889634f;
-    attn_bf16_kernel<<<dim3(n_tiles_q * Hq), kPPThreads, kSmemBytes, s>>>(
+    // Key shares need the caller's workspace for the partial results; without it (or with one
+    // that is too small or misaligned) the keys are not split, which is always valid.
+    int n_splits = choose_key_splits(Hq * n_tiles_q, ceil_div(Nk, kBN));
+    if (ws == nullptr || ws_bytes < attn_partial_bytes(Hq, Nq, n_splits) || reinterpret_cast<uintptr_t>(ws) % 16 != 0)
+      n_splits = 1;
+    float* part_o = nullptr;
+    float2* part_ml = nullptr;
+    if (n_splits > 1) {
+      part_o = static_cast<float*>(ws);
+      part_ml = reinterpret_cast<float2*>(static_cast<uint8_t*>(ws) +
+                                          align_up(static_cast<size_t>(n_splits) * Hq * Nq * kD * sizeof(float), 256));
+    }
+    attn_bf16_kernel<<<dim3(n_tiles_q * Hq * n_splits), kPPThreads, kSmemBytes, s>>>(
         static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
         static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), lse, rep, Nq, Nk, q_stride_h,
-        kv_stride_h, o_stride_h, c, n_tiles_q);
+        kv_stride_h, o_stride_h, c, n_tiles_q, n_splits, part_o, part_ml);
+    if (n_splits > 1) {
+      PC_CHECK_LAUNCH("pc_frame_attn");
+      attn_merge_kernel<<<static_cast<unsigned>((static_cast<int64_t>(Hq) * Nq + 7) / 8), 256, 0, s>>>(
+          part_o, part_ml, static_cast<uint16_t*>(O), lse, Hq, Nq, o_stride_h, n_splits);
+    }
   } else {
     PC_REQUIRE(D == 64 || D == 128, PC_ERR_UNSUPPORTED, "pc_frame_attn: fp32 tier needs D=64 or 128, got %d", D);
     const dim3 grid(ceil_div(Nq, kF32Threads), Hq);

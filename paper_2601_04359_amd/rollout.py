@@ -59,6 +59,9 @@ class RollingLayer:
         self.slide_t_scale, self.shift = slide_t_scale, 0
         n_rows = min(n_score, n_frame)
         self.q_rows = ((torch.arange(n_rows, dtype=torch.int64) * n_frame) // n_rows).to(torch.int32).to(device)
+        # room for the partial results of up to four key shares (the split depends on the key
+        # count of the call; a workspace that is too small only means no split)
+        self._ws_attn = torch.empty(4 * Hq * n_frame * (D * 4 + 8) + 1024, dtype=torch.uint8, device=device)
         if mode != "dense":   # the full-cache baseline neither scores nor compacts
             self.score = torch.empty((hsel, capacity), dtype=torch.float32, device=device)
             self._ws_score = torch.empty(pk.pc_score_workspace_bytes(Hq, Hkv, n_rows, capacity, share_heads),
@@ -125,7 +128,7 @@ class RollingLayer:
 
     def attend(self, Q, O=None, lse=None):
         """The (rotated) queries Q over the cache as it stands -> O (and the log-sum-exp)."""
-        return pk.pc_frame_attn(Q, self.K, self.V, self.nk, self.scale, O=O, lse=lse)
+        return pk.pc_frame_attn(Q, self.K, self.V, self.nk, self.scale, O=O, lse=lse, ws=self._ws_attn)
 
     def step(self, Q, O=None, q_pos=None, lse=None):
         """Queries Q [Hq][n_frame][D] of the frame being generated -> O.  q_pos (int32

@@ -169,6 +169,19 @@ def test_frame_attn_bf16_reference_maximum_is_refreshed(step):
     _attn_check("bf16", Q, K, V, d ** -0.5)
 
 
+@pytest.mark.parametrize("hq,hkv,nq,nk", [(6, 2, 300, 3000), (24, 8, 520, 2100), (3, 1, 40, 5000)])
+def test_frame_attn_bf16_key_shares_and_merge(hq, hkv, nq, nk):
+    # shapes whose work-group count fills the chip badly: the keys are cut into shares and
+    # merged (when a workspace is supplied); without one the un-split kernel must agree
+    Q, K, V = _attn_case("bf16", hq, hkv, nq, nk, 128, 5)
+    assert pk.pc_frame_attn_workspace_bytes(hq, nq, nk, 128) > 0
+    _attn_check("bf16", Q, K, V, 128 ** -0.5)                      # binding supplies the workspace
+    Qd, Kd, Vd = dev(Q, "bf16"), dev(K, "bf16"), dev(V, "bf16")
+    split = pk.pc_frame_attn(Qd, Kd, Vd, nk, 128 ** -0.5)
+    whole = pk.pc_frame_attn(Qd, Kd, Vd, nk, 128 ** -0.5, ws=torch.empty(16, dtype=torch.uint8, device=DEV))
+    assert (split.float() - whole.float()).abs().max().item() <= 2 ** -6   # two roundings of values of O(1)
+
+
 def test_frame_attn_bf16_closed_forms():
     Q, K, V = _attn_case("bf16", 2, 1, 70, 200, 128, 3)
     Ke = np.repeat(K[:, :1], 200, axis=1)                     # all keys equal -> mean of V
