@@ -269,8 +269,12 @@ int pc_mask_scores(float* score, int Hsel, int Nk, int64_t score_stride_h, const
  * is applied.  The same call serves the packed and the full ("dense") cache.
  *   Q  dev [Hq][Nq][D], K, V dev [Hkv][Nk][D], O dev [Hq][Nq][D] (dtype; bf16 is rounded
  *   to nearest even), lse dev or NULL fp32 [Hq][Nq] = ln sum_j exp(scale * q.k_j).
+ *   ws  dev or NULL: optional.  With a workspace of pc_frame_attn_workspace_bytes (0 for most
+ *   shapes) the bf16 kernel may cut the keys into shares when Hq * ceil(Nq / 256) work-groups
+ *   would fill the chip badly, and merge the partial results; without it (or with one that is
+ *   too small) the keys are not split.  Results agree to the rounding of the output.
  * Nk >= 1, Nq >= 1.  Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE, PC_ERR_UNSUPPORTED,
- * PC_ERR_WORKSPACE, PC_ERR_HIP.
+ * PC_ERR_HIP.
  */
 size_t pc_frame_attn_workspace_bytes(int Hq, int Nq, int Nk, int D);
 int pc_frame_attn(const void* Q, const void* K, const void* V, int dtype, int Hq, int Hkv,
