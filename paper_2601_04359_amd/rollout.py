@@ -121,10 +121,13 @@ class RollingLayer:
         stands, e.g. from attend(): scoring then needs one QK^T pass instead of two."""
         if self.mode == "dense":
             return
+        budgets = self.budgets()
+        if all(b >= s[1] for s, b in zip(self.segments, budgets) if s[2] == pk.PC_SEG_FRAME):
+            return   # every frame is within its budget: nothing to score, nothing to move
         pk.pc_score(Q, self.K, self.nk, self.scale, lse=lse, score=self.score, share_heads=self.share_heads,
                     ws=self._ws_score, q_rows=self.q_rows)
         self.segments, self.nk = pk.pc_compact(self.K, self.V, self.pos, self.score, self.segments,
-                                               self.budgets(), share_heads=self.share_heads, ws=self._ws_compact)
+                                               budgets, share_heads=self.share_heads, ws=self._ws_compact)
 
     def attend(self, Q, O=None, lse=None):
         """The (rotated) queries Q over the cache as it stands -> O (and the log-sum-exp)."""
