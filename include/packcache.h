@@ -42,7 +42,8 @@ typedef enum pc_status {
   PC_ERR_UNSUPPORTED = -4, /* valid request the kernels do not cover (e.g. bf16 with D != 128) */
   PC_ERR_BUDGET = -5,      /* negative budget, bad decay factor or mode */
   PC_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than *_workspace_bytes says */
-  PC_ERR_HIP = -7          /* a HIP runtime call or kernel launch failed */
+  PC_ERR_HIP = -7,         /* a HIP runtime call or kernel launch failed */
+  PC_ERR_ABORTED = -8      /* pc_compact_status: an in-place gather gave up its bounded wait */
 } pc_status;
 
 enum { PC_F32 = 0, PC_BF16 = 1 };
@@ -187,7 +188,7 @@ int pc_compact_plan(const pc_segment* seg_in, int n_seg, const int32_t* budget,
  * run concurrently must not share a workspace, and a workspace must not be reused by another
  * stream before the call that uses it has finished.  The spin bound cannot be hit while the
  * workspace is used by one call at a time; if it is, the waiting work-groups give up, the
- * result of that call is undefined and nothing hangs.
+ * result of that call is undefined, nothing hangs, and pc_compact_status reports it.
  * Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE (n_seg > PC_MAX_SEGMENTS, strides,
  * table), PC_ERR_BUDGET, PC_ERR_WORKSPACE, PC_ERR_HIP.
  */
@@ -241,6 +242,16 @@ int pc_compact_batch_phase(int phases, int n_layers, void* K, void* V, int32_t* 
                            int64_t pos_out_stride_h, int64_t pos_out_stride_l, int32_t* idx_out,
                            int64_t idx_stride_h, int64_t idx_stride_l, pc_segment* seg_out,
                            int32_t* Nk_out, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * pc_compact_status -- did the last in-place compaction that used workspace `ws` run to the
+ * end?  Waits for `stream` (the stream that compaction was enqueued on), reads one word of
+ * the workspace back and returns PC_OK, or PC_ERR_ABORTED when a work-group hit the spin bound
+ * of its wait (the packed rows of that call are then not to be trusted).  The word is reset by
+ * the next compaction call on the workspace.  For callers that want the check; the path itself
+ * never needs it.  Errors: PC_ERR_NULL, PC_ERR_HIP, PC_ERR_ABORTED.
+ */
+int pc_compact_status(const void* ws, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * Cache mask (Sec. 3.1: a binary mask says which generated tokens are visible to later

@@ -13,7 +13,7 @@ __all__ = [
     "PC_F32", "PC_BF16", "PC_SEG_TEXT", "PC_SEG_COND", "PC_SEG_FRAME", "PC_SEG_SELF",
     "PC_BUDGET_POW", "PC_BUDGET_NORM", "PC_BUDGET_HALF", "PC_BUDGET_SLIDE", "PC_MAX_SEGMENTS",
     "PackCacheError", "lib", "lib_path", "pc_version", "pc_strerror", "pc_budget", "pc_rope3d", "pc_rebase",
-    "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact", "pc_compact_batch", "pc_compact_batch_workspace_bytes", "PC_COMPACT_SELECT", "PC_COMPACT_GATHER", "pc_masked_budgets", "pc_mask_scores",
+    "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact", "pc_compact_batch", "pc_compact_batch_workspace_bytes", "PC_COMPACT_SELECT", "PC_COMPACT_GATHER", "pc_masked_budgets", "pc_mask_scores", "pc_compact_status",
     "pc_compact_workspace_bytes", "pc_compact_prepared", "pc_frame_attn", "pc_frame_attn_workspace_bytes",
     "segment_budgets",
 ]
@@ -74,6 +74,7 @@ def lib() -> C.CDLL:
         L.pc_compact_batch_phase.argtypes = [C.c_int] + list(L.pc_compact_batch.argtypes)
         L.pc_masked_budgets.argtypes = [segp, C.c_int, i32p, vp, i32p]
         L.pc_mask_scores.argtypes = [vp, C.c_int, C.c_int, i64, vp, vp]
+        L.pc_compact_status.argtypes = [vp, vp]
         L.pc_compact_plan.argtypes = [segp, C.c_int, i32p, segp, i32p]
         L.pc_compact_workspace_bytes.restype = sz
         L.pc_compact_workspace_bytes.argtypes = [C.c_int] * 3
@@ -212,6 +213,12 @@ def pc_mask_scores(score, valid) -> None:
     """score fp32 [Hsel][Nk] (device), valid uint8 [Nk] (device): masked tokens get -1."""
     _check(lib().pc_mask_scores(score.data_ptr(), score.shape[0], score.shape[1], score.stride(0),
                                 valid.data_ptr(), _stream()))
+
+
+def pc_compact_status(ws, stream=None) -> None:
+    """Waits for the stream and raises (status PC_ERR_ABORTED) if the last in-place compaction that
+    used the workspace tensor `ws` gave up a wait."""
+    _check(lib().pc_compact_status(ws.data_ptr(), _stream() if stream is None else stream))
 
 
 def pc_compact_plan(segments, budgets):

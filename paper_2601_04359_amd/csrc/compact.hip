@@ -16,6 +16,7 @@
 //            nothing.
 //   A stack of layers is handled by the same two launches (layer strides).
 #include <limits.h>
+#include <stddef.h>
 
 #include <algorithm>
 
@@ -428,21 +429,24 @@ __global__ void mask_scores_kernel(float* __restrict__ score, int64_t score_stri
 }
 
 struct WsLayout {
-  size_t idx_off, sync_off, flags_off, total;
+  size_t idx_off, sync_off, flags_off, clear_bytes, total;
   int chunks_per_head;
 };
 
 WsLayout ws_layout(int n_layers, int Hkv, int Nk_in, int share_heads) {
   WsLayout w;
   const int hsel = share_heads ? 1 : Hkv;
+  // the bookkeeping leads (pc_compact_status reads the abort word at offset 0); the flags follow
+  // it directly, so one contiguous range is cleared per call
   size_t at = 0;
-  w.idx_off = at;
-  at += align_up(sizeof(int32_t) * static_cast<size_t>(n_layers) * hsel * Nk_in, 256);
   w.sync_off = at;
-  at += sizeof(GatherSync);
+  at += align_up(sizeof(GatherSync), 256);
   w.flags_off = at;
   w.chunks_per_head = ceil_div(Nk_in, kGatherRows);
   at += align_up(sizeof(int32_t) * static_cast<size_t>(n_layers) * Hkv * w.chunks_per_head, 256);
+  w.clear_bytes = at;
+  w.idx_off = at;
+  at += align_up(sizeof(int32_t) * static_cast<size_t>(n_layers) * hsel * Nk_in, 256);
   w.total = at;
   return w;
 }
@@ -583,7 +587,7 @@ extern "C" int pc_compact_batch_phase(int phases, int n_layers, void* K, void* V
   const dim3 sgrid(n_seg, hsel * n_layers);
   // the select kernel also clears the in-place gather's counters and flags (contiguous in ws)
   int32_t* clear = in_place ? reinterpret_cast<int32_t*>(sync) : nullptr;
-  const int n_clear = in_place ? static_cast<int>((lay.total - lay.sync_off) / sizeof(int32_t)) : 0;
+  const int n_clear = in_place ? static_cast<int>(lay.clear_bytes / sizeof(int32_t)) : 0;
   if (!(phases & PC_COMPACT_SELECT)) {
     // indices and cleared counters come from an earlier SELECT call with the same arguments
   } else if (max_prune_len <= 256)
@@ -631,6 +635,19 @@ extern "C" int pc_compact_batch_phase(int phases, int n_layers, void* K, void* V
   }
 #undef PC_LAUNCH_GATHER
   PC_CHECK_LAUNCH("pc_compact gather");
+  return PC_OK;
+}
+
+extern "C" int pc_compact_status(const void* ws, void* stream) {
+  PC_REQUIRE(ws != nullptr, PC_ERR_NULL, "pc_compact_status: ws is NULL");
+  static_assert(offsetof(GatherSync, abort) == 0, "the abort word leads the workspace");
+  int32_t word = 0;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipError_t e = hipMemcpyAsync(&word, ws, sizeof(word), hipMemcpyDeviceToHost, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  PC_REQUIRE(e == hipSuccess, PC_ERR_HIP, "pc_compact_status: %s", hipGetErrorString(e));
+  PC_REQUIRE(word == 0, PC_ERR_ABORTED,
+             "pc_compact_status: an in-place gather gave up waiting (workspace shared by overlapping calls?)");
   return PC_OK;
 }
 

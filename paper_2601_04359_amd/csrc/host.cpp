@@ -176,13 +176,14 @@ extern "C" const char* pc_strerror(int status) {
     case PC_ERR_BUDGET: return "invalid budget, decay factor or budget mode";
     case PC_ERR_WORKSPACE: return "workspace missing or too small";
     case PC_ERR_HIP: return "HIP runtime error";
+    case PC_ERR_ABORTED: return "in-place compaction gave up a wait";
     default: return "unknown status";
   }
 }
 
 extern "C" const char* pc_last_error_detail(void) { return g_detail; }
 
-extern "C" int pc_version(void) { return 101; }
+extern "C" int pc_version(void) { return 102; }
 
 extern "C" int pc_budget(int mode, int n_frame_tokens, int n_past, double gamma, int b_min,
                          int32_t* budget_out) {

@@ -330,6 +330,29 @@ def _compact_run(w, sc, budgets, in_place, share=False, hsel=None):
     return host(Ko), host(Vo), host(po), host(idx), segs
 
 
+def test_compact_status_reports_the_abort_word():
+    """pc_compact_status is PC_OK after an ordinary in-place call; the abort word (set here from the
+    host, never by making a kernel wait in vain) turns into PC_ERR_ABORTED; the next call resets it."""
+    w = synth.midsize()
+    sc = dev(np.random.default_rng(5).random((w.Hkv, w.Nk)).astype(np.float32), None)
+    budgets = budgets_for(w)
+    ws = torch.empty(pk.pc_compact_workspace_bytes(w.Hkv, w.Nk), dtype=torch.uint8, device=DEV)
+
+    def run():
+        K, V = dev(w.K, w.dtype), dev(w.V, w.dtype)
+        pos = dev(np.broadcast_to(w.pos_k[None], (w.Hkv, w.Nk, 3)).copy(), None)
+        pk.pc_compact(K, V, pos, sc, w.segments, budgets, ws=ws)
+
+    run()
+    pk.pc_compact_status(ws)
+    ws[:4].view(torch.int32).fill_(1)
+    with pytest.raises(pk.PackCacheError) as e:
+        pk.pc_compact_status(ws)
+    assert e.value.status == -8
+    run()
+    pk.pc_compact_status(ws)
+
+
 @pytest.mark.parametrize("in_place", [False, True])
 @pytest.mark.parametrize("case", ["c1", "mid", "mid_f32"])
 def test_compact_matches_oracle_on_given_scores(case, in_place):

@@ -180,6 +180,9 @@ def test_batched_compaction_and_mask_argument_checks(L):
     assert L.pc_mask_scores(one, 2, 10, 9, one, None) == -2
     assert L.pc_mask_scores(None, 0, 10, 10, None, None) == 0
     assert L.pc_masked_budgets(seg, 2, bud, None, bud) == -1
+    # status of a workspace that does not exist
+    assert L.pc_compact_status(None, None) == -1
+    assert L.pc_strerror(-8) not in (None, L.pc_strerror(-7))
 
 
 def test_bench_refuses_more_than_one_gpu():
