@@ -133,11 +133,12 @@ __global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ sc
 // bits at a time: keys that still match the prefix vote into a 256-bin LDS histogram, the
 // 256 threads take a suffix sum over the bins (wave scan + one exchange) and the bin that
 // contains the k-th key extends the prefix; as soon as that bin holds a single key, the
-// key itself is the threshold and the remaining passes are skipped.  Scores of one segment
-// crowd into a few bins on the leading bits, so the histogram is kept in 32 copies laid out
-// [bin][lane % 32]: a vote lands in the voter's own LDS bank and votes of one instruction
-// never queue behind each other.  The ordered output needs one more exchange (keys above
-// the threshold and keys equal to it, per wave).
+// key itself is the threshold and the remaining passes are skipped.  The histogram is kept in
+// four copies laid out [bin][lane % 4], which spreads the votes of one instruction for a crowded
+// bin over four addresses; more copies cost more to clear and to add up than the shorter
+// queues save once a stack of layers fills the chip with these work-groups (the kernel is then
+// bound by its instruction count).  The ordered output needs one more exchange (keys above the
+// threshold and keys equal to it, per wave).
 // Blocks also clear the in-place gather's ticket counters and flags (n_clear words).
 template <int kItems>
 __global__ __launch_bounds__(256) void select_block_kernel(const float* __restrict__ score,
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
                                                            SegTable tab, int32_t* __restrict__ clear,
                                                            int n_clear, int hsel, int64_t score_stride_l,
                                                            int64_t idx_stride_l) {
-  constexpr int kCopies = 32;
+  constexpr int kCopies = 4;
   __shared__ __align__(16) int s_hist[256 * kCopies];
   __shared__ int s_wave_sum[4];
   __shared__ int s_pick[4];  // chosen digit, keys above it, keys in it, the key when it is alone
@@ -203,11 +204,7 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
   int remaining = k;
   while (hi > 0) {
     const int width = min(8, hi), shift = hi - width;
-    {
-      int4* h4 = reinterpret_cast<int4*>(s_hist);
-#pragma unroll
-      for (int i = 0; i < 256 * kCopies / 4 / 256; ++i) h4[i * 256 + threadIdx.x] = make_int4(0, 0, 0, 0);
-    }
+    reinterpret_cast<int4*>(s_hist)[threadIdx.x] = make_int4(0, 0, 0, 0);  // bin threadIdx.x, all copies
     __syncthreads();
     const uint32_t hi_mask = hi >= 32 ? 0u : 0xFFFFFFFFu << hi;
     const uint32_t digit_mask = (1u << width) - 1u;
@@ -218,9 +215,9 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
         atomicAdd(&s_hist[((key[i] >> shift) & digit_mask) * kCopies + (lane & (kCopies - 1))], 1);
     }
     __syncthreads();
-    int mine = 0;  // votes for bin threadIdx.x; the rotation keeps the reads of a wave on distinct banks
-#pragma unroll
-    for (int j = 0; j < kCopies; ++j) mine += s_hist[threadIdx.x * kCopies + ((j + threadIdx.x) & (kCopies - 1))];
+    static_assert(kCopies == 4, "a thread adds up its bin's copies with one 16-byte read");
+    const int4 votes = reinterpret_cast<const int4*>(s_hist)[threadIdx.x];
+    const int mine = votes.x + votes.y + votes.z + votes.w;  // votes for bin threadIdx.x
     // suffix sums: above = number of matching keys with a digit larger than this thread's
     int incl = mine;  // inclusive suffix sum inside the wave (towards higher lanes)
 #pragma unroll
@@ -306,10 +303,13 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     int chunks_per_head, SegTable tab, int n_layers, int64_t in_stride_lc, int64_t out_stride_lc,
     int64_t pos_stride_l, int64_t pos_out_stride_l, int64_t idx_stride_l) {
   __shared__ int s_ticket;
-  const int n_vh = Hkv * n_layers;       // (layer, KV head) pairs
-  const int vh = blockIdx.x % n_vh;
-  const int l = vh / Hkv, h = vh % Hkv;
-  int cc = blockIdx.x / n_vh;
+  // launch order: layer by layer, the KV heads of a layer side by side (a few long sequential
+  // streams at a time suit the memory better than one stream per (layer, head) all at once)
+  const int per_layer = gridDim.x / n_layers;
+  const int l = blockIdx.x / per_layer, in_layer = blockIdx.x % per_layer;
+  const int h = in_layer % Hkv;
+  const int vh = l * Hkv + h;            // (layer, KV head) pair
+  int cc = in_layer / Hkv;
   if constexpr (kInPlace) {  // chunks of a head are taken in ticket order, not in launch order
     if (threadIdx.x == 0) s_ticket = atomicAdd(&sync->ticket[vh][0], 1);
     __syncthreads();
