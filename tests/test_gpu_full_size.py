@@ -10,6 +10,8 @@ Each step is compared with the fp64 oracle on identical input bits:
     as in the frame-48 compaction runs, for gamma in {0.7, 0.85, 0.95};
   * pc_frame_attn, packed and dense, on 64 sampled query rows per head over all keys
     (max |err| <= 2e-2, mean |err| <= 2e-3), and its log-sum-exp output.
+The rolling step (cache packed in place over several frame steps) is checked at the 28-layer
+rollout's shape, 24 query / 8 KV heads, each step starting from the oracle's previous state.
 The steps after the rotation read the ORACLE's rotated bits, so that every step is judged on
 inputs identical to the oracle's; the chained device path is covered at reduced size in
 test_gpu_parity.py.
@@ -121,3 +123,93 @@ def test_full_size_frame(frame):
     err = np.abs(host(O)[:, rs].astype(np.float64) - Ow)
     assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
     assert np.abs(host(lse)[:, rs] - Lw).max() <= 1e-3
+
+
+def test_rolling_steps_at_full_frame_size():
+    """The rolling step at the shape of the 28-layer rollout: 24 query / 8 KV heads, 48x84-token
+    frames, 256 text tokens, 512 scoring rows, gamma 0.85 with a 512-token minimum, cache packed
+    in place, attention cut into key shares.  Every step starts from the ORACLE's cache after the
+    previous step (so a selection that falls inside the score band cannot carry over), and is
+    compared with the oracle's next state: segment table, kept rows (bit-exact outside the band),
+    moved K / V / positions, and the attention of 64 sampled query rows per head."""
+    from paper_2601_04359_amd.rollout import RollingLayer
+    gamma, b_min, n_steps = 0.85, 512, 4
+    case = synth.rolling_case(seed=7, n_steps=n_steps, hq=24, hkv=8, d=128, n_text=256, gh=48, gw=84, n_score=512)
+    rnd = orc.round_to_bf16
+    aK = rnd(orc.rope3d(case.anchor_K, case.anchor_pos, case.sections, case.base))
+    frames = [(rnd(orc.rope3d(K, p, case.sections, case.base)), V, p) for K, V, p in case.frames]
+    queries = [rnd(orc.rope3d(Q, p, case.sections, case.base)) for Q, p in zip(case.queries, case.query_pos)]
+    n, Hkv = case.n_frame, case.Hkv
+    rows = np.union1d(case.score_rows, synth.strided_rows(n, N_SAMPLE_ROWS))   # the rows the oracle is given
+    score_sub = np.searchsorted(rows, case.score_rows)
+    sample_sub = np.searchsorted(rows, synth.strided_rows(n, N_SAMPLE_ROWS))
+    budget_fn = lambda w: orc.budget_pow(n, w, gamma, b_min)
+    want = orc.rolling_rollout(aK, case.anchor_V, case.anchor_pos, case.anchor_segments, frames,
+                               [Q[:, rows] for Q in queries], case.scale, budget_fn, score_rows=score_sub)
+    capacity = case.anchor_K.shape[1] + n_steps * n
+
+    def insert(layer, K, V, pos_h, kind, frame):
+        m = K.shape[1]
+        k, v, pp = layer.reserve(m)
+        k.copy_(dev(np.asarray(K, dtype=np.float32), "bf16"))
+        v.copy_(dev(np.asarray(V, dtype=np.float32), "bf16"))
+        pp.copy_(dev(np.ascontiguousarray(pos_h, dtype=np.int32), None))
+        layer.commit(m, kind, frame)
+
+    exempted = 0
+    for i, Q in enumerate(queries):
+        layer = RollingLayer(case.Hq, Hkv, case.D, capacity, n, case.scale, mode="pow", gamma=gamma, b_min=b_min,
+                             n_score=case.score_rows.size, sections=case.sections, base=case.base, device=DEV)
+        assert np.array_equal(host(layer.q_rows), case.score_rows)
+        if i == 0:
+            pre = {"K": aK, "V": case.anchor_V, "segments": list(case.anchor_segments),
+                   "pos": np.broadcast_to(case.anchor_pos[None], (Hkv,) + case.anchor_pos.shape)}
+        else:
+            pre = want[i - 1]
+        for (start, length, kind, frame) in pre["segments"]:
+            insert(layer, pre["K"][:, start:start + length], pre["V"][:, start:start + length],
+                   pre["pos"][:, start:start + length], kind, frame)
+        if i >= 1:
+            Kf, Vf, pf = frames[i - 1]
+            insert(layer, Kf, Vf, np.broadcast_to(pf[None], (Hkv,) + pf.shape), pk.PC_SEG_FRAME, i)
+        segs_pre, nk_pre = list(layer.segments), layer.nk
+        K_pre, V_pre, pos_pre = (np.asarray(pre[k], dtype=t) for k, t in (("K", np.float64), ("V", np.float64),
+                                                                          ("pos", np.int32)))
+        if i >= 1:
+            K_pre, V_pre = np.concatenate([K_pre, Kf], 1), np.concatenate([V_pre, Vf.astype(np.float64)], 1)
+            pos_pre = np.concatenate([pos_pre, np.broadcast_to(pf[None], (Hkv,) + pf.shape)], 1)
+        assert np.array_equal(host(layer.K[:, :nk_pre]), K_pre) and np.array_equal(host(layer.V[:, :nk_pre]), V_pre)
+        assert np.array_equal(host(layer.pos[:, :nk_pre]), pos_pre)    # the device starts from the oracle's bits
+        O = layer.step(dev(Q.astype(np.float32), "bf16"))
+        w = want[i]
+        nk = layer.nk
+        assert layer.segments == w["segments"] and nk == w["K"].shape[1], i
+        pos_got = host(layer.pos[:, :nk])
+        # source row of every kept row: (t, h, w) is unique inside the cache
+        code = lambda p: (p[..., 0].astype(np.int64) * 4096 + p[..., 1]) * 4096 + p[..., 2]
+        idx = np.empty((Hkv, nk), dtype=np.int64)
+        for h in range(Hkv):
+            order = np.argsort(code(pos_pre[h]), kind="stable")
+            at = np.searchsorted(code(pos_pre[h])[order], code(pos_got[h]))
+            idx[h] = order[at]
+            assert np.array_equal(pos_pre[h][idx[h]], pos_got[h])
+        if not np.array_equal(pos_got, w["pos"]):   # allowed only inside the score band
+            n_past = sum(1 for s in segs_pre if s[2] == pk.PC_SEG_FRAME)
+            per_d = budget_fn(n_past)
+            budgets, d = [], n_past
+            for s in segs_pre:
+                budgets.append(per_d[d - 1] if s[2] == pk.PC_SEG_FRAME else s[1])
+                d -= s[2] == pk.PC_SEG_FRAME
+            sco = orc.score(Q[:, case.score_rows], K_pre, case.scale)
+            exempted += check_selection(idx, sco, segs_pre, budgets, band=BAND)
+        Kg, Vg = host(layer.K[:, :nk]).astype(np.float64), host(layer.V[:, :nk]).astype(np.float64)
+        for h in range(Hkv):
+            assert np.array_equal(Kg[h], K_pre[h][idx[h]]) and np.array_equal(Vg[h], V_pre[h][idx[h]])
+        Ow, _ = orc.frame_attn(Q[:, rows[sample_sub]], Kg, Vg, case.scale)
+        err = np.abs(host(O)[:, rows[sample_sub]].astype(np.float64) - Ow)
+        assert err.max() <= 2e-2 and err.mean() <= 2e-3, (i, err.max(), err.mean())
+        if np.array_equal(pos_got, w["pos"]):
+            err = np.abs(host(O)[:, rows].astype(np.float64) - w["O"])
+            assert err.max() <= 2e-2 and err.mean() <= 2e-3, (i, err.max(), err.mean())
+        print(f"step {i + 1}: Nk {nk_pre} -> {nk}, band-exempt keys so far {exempted}", flush=True)
+        del layer
