@@ -681,3 +681,55 @@ def test_random_segment_tables_batched_in_and_out_of_place():
         pk.pc_compact_batch(K, V, pos, sc, segs, budgets, share_heads=share, idx=i2)
         assert torch.equal(i2, io) and torch.equal(K[:, :, :nko], Ko) and torch.equal(V[:, :, :nko], Vo)
         assert torch.equal(pos[:, :, :nko], po), it
+
+
+def test_step_captured_in_a_hip_graph_replays_to_the_eager_result():
+    """The whole step (restore, a1..a6, compaction in place, key shares in the attention) recorded
+    into a HIP graph on a side stream and replayed several times, with eager work and
+    synchronisations in between: every replay must give the eager run's bits (the kernels are
+    deterministic, nothing in the calls allocates or synchronises when workspaces are passed, and
+    the in-place bookkeeping is cleared by a kernel, not by a memset node)."""
+    w = synth.midsize(n_past=14, gamma=0.95)     # 2,740 keys stay: the attention cuts them into two shares
+    dt = w.dtype
+    Q0, K0, V0 = dev(w.Q, dt), dev(w.K, dt), dev(w.V, dt)
+    pos0 = dev(np.broadcast_to(w.pos_k[None], (w.Hkv, w.Nk, 3)).copy(), None)
+    Q, K, V, pos = Q0.clone(), K0.clone(), V0.clone(), pos0.clone()
+    pos_q, newest = dev(w.pos_q, None), w.segments[-1]
+    pos_new = dev(w.pos_k[newest[0]:newest[0] + newest[1]], None)
+    rows = dev(w.score_rows.astype(np.int32), None)
+    budgets = budgets_for(w)
+    nk_out = pk.pc_compact_plan(w.segments, budgets)[1]
+    sc = torch.empty((w.Hkv, w.Nk), dtype=torch.float32, device=DEV)
+    O, lse = torch.empty_like(Q), torch.empty((w.Hq, w.Nq), dtype=torch.float32, device=DEV)
+    ws_s = torch.empty(pk.pc_score_workspace_bytes(w.Hq, w.Hkv, rows.numel(), w.Nk), dtype=torch.uint8, device=DEV)
+    ws_c = torch.empty(pk.pc_compact_workspace_bytes(w.Hkv, w.Nk), dtype=torch.uint8, device=DEV)
+    n_ws_a = pk.pc_frame_attn_workspace_bytes(w.Hq, w.Nq, nk_out, w.D)
+    assert n_ws_a > 0, "this shape is meant to take the key-share path"
+    ws_a = torch.empty(n_ws_a, dtype=torch.uint8, device=DEV)
+
+    def step():
+        Q.copy_(Q0), K.copy_(K0), V.copy_(V0), pos.copy_(pos0)
+        pk.pc_rope3d(Q, pos_q, w.sections, w.base)
+        pk.pc_rope3d(K[:, newest[0]:newest[0] + newest[1]], pos_new, w.sections, w.base)
+        pk.pc_score(Q, K, w.Nk, w.scale, score=sc, ws=ws_s, q_rows=rows)
+        segs, nk = pk.pc_compact(K, V, pos, sc, w.segments, budgets, ws=ws_c)
+        assert nk == nk_out
+        pk.pc_frame_attn(Q, K, V, nk, w.scale, O=O, lse=lse, ws=ws_a)
+
+    step()                                   # eager; also the first-use set-up of every kernel
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (O, lse, K[:, :nk_out], V[:, :nk_out], pos[:, :nk_out], sc)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for replay in range(4):
+        for t in (O, lse, sc):               # eager work between the replays: scribble on the outputs
+            t.fill_(float(replay + 7))
+        K.zero_(), pos.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (O, lse, K[:, :nk_out], V[:, :nk_out], pos[:, :nk_out], sc)
+        for i, (g, x) in enumerate(zip(got, want)):
+            assert torch.equal(g, x), f"replay {replay}: output {i} differs from the eager run"
+    pk.pc_compact_status(ws_c)
