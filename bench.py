@@ -406,6 +406,12 @@ def main() -> int:
                           "speedup_total": round(td / tp, 3),
                           "speedup_last4": round(sum(r["dense_ms"] for r in last4) / sum(r["packed_ms"] for r in last4), 3),
                           "last_frame": curve[-1],
+                          # K and V rows resident per layer at the last step (Fig. 7: the packed cache is
+                          # bounded, the full cache grows with the frame index); allocation is cap_* rows
+                          "kv_cache_MB_per_layer": {"packed": round(packed[0].nk * hkv5 * D * 2 * 2 / 1e6, 1),
+                                                    "dense": round(dense[0].nk * hkv5 * D * 2 * 2 / 1e6, 1),
+                                                    "packed_allocated": round(cap_packed * hkv5 * D * 2 * 2 / 1e6, 1),
+                                                    "dense_allocated": round(cap_dense * hkv5 * D * 2 * 2 / 1e6, 1)},
                           "note": "packed_ms covers rope, score, budget, in-place compaction and attention of all "
                                   "layers; dense_ms rope and attention over the full cache"}
         os.makedirs(args.out_dir, exist_ok=True)
