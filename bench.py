@@ -59,6 +59,10 @@ def main() -> int:
     ap.add_argument("--out-dir", default=os.path.join(ROOT, "gpurun_out"), help="where the per-frame tables go")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-f48", action="store_true", help="skip the frame-48 compaction / dense legs")
+    ap.add_argument("--no-fold", action="store_true",
+                    help="keep the softmax scale out of the queries: pc_score / pc_frame_attn then multiply "
+                         "every product element by it (the general loop); default: the query rotation folds "
+                         "scale * log2(e) into Q and the calls get scale = ln 2")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the dense frame-24 comparison call, so that a profile of this command "
                          "sees pc_frame_attn at the packed shape only")
@@ -124,18 +128,25 @@ def main() -> int:
     k_new = K[:, newest[0]:newest[0] + newest[1]]
     kept_past_rows = nk_packed - (w.n_text + w.n_frame)
 
+    # The softmax scale rides on the query rotation (one rounding either way); the scoring and
+    # attention calls then see scale = ln 2 and run their shorter loops.  Same softmax(QK^T/sqrt(D)).
+    fold = not args.no_fold
+    q_out_scale = pk.folded_q_scale(w.scale) if fold else 1.0
+    call_scale = pk.PC_SCALE_FOLDED if fold else w.scale
+
     ev_attn = []
 
     def step(record=False):
-        pk.pc_rope3d(Q, pos_q, w.sections, w.base)
+        Q.copy_(Q0)          # the step's queries arrive un-rotated
+        pk.pc_rope3d(Q, pos_q, w.sections, w.base, out_scale=q_out_scale)
         pk.pc_rope3d(k_new, pos_new, w.sections, w.base)
-        pk.pc_score(Q, K, Nk, w.scale, score=score, ws=ws_s, q_rows=rows)
+        pk.pc_score(Q, K, Nk, call_scale, score=score, ws=ws_s, q_rows=rows)
         b = pk.segment_budgets(w.segments, pk.pc_budget(pk.PC_BUDGET_POW, w.n_frame, w.n_past, w.gamma, w.b_min))
         _, nk = pk.pc_compact(K, V, pos, score, w.segments, b, out=(Kp, Vp, pp), ws=ws_c)
         if record:
             a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record()
-        pk.pc_frame_attn(Q, Kp, Vp, nk, w.scale, O=O)
+        pk.pc_frame_attn(Q, Kp, Vp, nk, call_scale, O=O)
         if record:
             e.record()
             ev_attn.append((a, e))
@@ -153,11 +164,13 @@ def main() -> int:
     attn_tflops = fl_packed / (attn_ms * 1e-3) / 1e12
 
     # the other steps of the path, one by one (same stream, events around each call)
-    rope_ms = timed(lambda: (pk.pc_rope3d(Q, pos_q, w.sections, w.base),
+    Qr = Q0.clone()          # rotated over and over here: plain rotation, so that it keeps its magnitude
+    rope_ms = timed(lambda: (pk.pc_rope3d(Qr, pos_q, w.sections, w.base),
                              pk.pc_rope3d(k_new, pos_new, w.sections, w.base)), 10)
-    score_ms = timed(lambda: pk.pc_score(Q, K, Nk, w.scale, score=score, ws=ws_s, q_rows=rows), 10)
+    del Qr
+    score_ms = timed(lambda: pk.pc_score(Q, K, Nk, call_scale, score=score, ws=ws_s, q_rows=rows), 10)
     compact_ms = timed(lambda: pk.pc_compact(K, V, pos, score, w.segments, budgets, out=(Kp, Vp, pp), ws=ws_c), 10)
-    dense_ms = None if args.no_dense else timed(lambda: pk.pc_frame_attn(Q, K, V, Nk, w.scale, O=O), 3)
+    dense_ms = None if args.no_dense else timed(lambda: pk.pc_frame_attn(Q, K, V, Nk, call_scale, O=O), 3)
     score_flops = 2.0 * 2.0 * D * rows.numel() * Hq * Nk          # two QK^T passes
     out = {
         "metric": "packed frame-attn ms/layer + TFLOP/s (% MFMA peak); compaction GB/s at 48 frames",
@@ -169,7 +182,7 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "configs[1]: single layer at frame 24", "Hq": Hq, "Hkv": Hkv, "D": D,
                    "Nq": Nq, "Nk_dense": Nk, "Nk_packed": nk_packed, "gamma": w.gamma, "b_min": w.b_min,
-                   "score_queries": int(rows.numel())},
+                   "score_queries": int(rows.numel()), "scale_folded_into_q": fold},
         "attn_packed_ms_per_layer": round(attn_ms, 4),
         "attn_dense_ms_per_layer": dense_ms and round(dense_ms, 4),
         "attn_dense_tflops": dense_ms and round(attn_flops(Hq, Nq, Nk, D) / (dense_ms * 1e-3) / 1e12, 2),
@@ -191,11 +204,13 @@ def main() -> int:
         w48 = synth.config2(seed=1001, n_past=47)
         Nk48 = w48.Nk
         K48, V48, Q48 = up(w48.K), up(w48.V), up(w48.Q)
+        if fold:             # as the rotation with out_scale leaves them
+            Q48 = (Q48.float() * q_out_scale).to(torch.bfloat16)
         pos48 = up(np.broadcast_to(w48.pos_k[None], (Hkv, Nk48, 3)).copy(), bf=False)
         rows48 = up(w48.score_rows.astype(np.int32), bf=False)
         ws_s48 = torch.empty(pk.pc_score_workspace_bytes(Hq, Hkv, rows48.numel(), Nk48), dtype=torch.uint8, device=dev)
         ws_c48 = torch.empty(pk.pc_compact_workspace_bytes(Hkv, Nk48), dtype=torch.uint8, device=dev)
-        sc48 = pk.pc_score(Q48, K48, Nk48, w48.scale, ws=ws_s48, q_rows=rows48)
+        sc48 = pk.pc_score(Q48, K48, Nk48, call_scale, ws=ws_s48, q_rows=rows48)
         O48 = torch.empty_like(Q48)
         # Compaction only: 28 layers (copies of the cache) compacted in place back to back as one
         # stream-ordered batch; algorithmic bytes of all layers over the time of the batch.
@@ -273,11 +288,11 @@ def main() -> int:
                     KL[0].copy_(K48), VL[0].copy_(V48), PL[0].copy_(pos48)
                     c()                                                # layer 0 packed at gamma 0.85 again
                 Kw, Vw = layers[0][0], layers[0][1]
-                packed48_ms = timed(lambda: pk.pc_frame_attn(Q48, Kw, Vw, nk48p, w48.scale, O=O48), 3)
+                packed48_ms = timed(lambda: pk.pc_frame_attn(Q48, Kw, Vw, nk48p, call_scale, O=O48), 3)
                 nk48_packed = nk48p
         Kw, Vw, pw = layers[0][0], layers[0][1], layers[0][2]
-        dense48_ms = timed(lambda: pk.pc_frame_attn(Q48, K48, V48, Nk48, w48.scale, O=O48), 2)
-        score48_ms = timed(lambda: pk.pc_score(Q48, K48, Nk48, w48.scale, score=sc48, ws=ws_s48, q_rows=rows48), 3)
+        dense48_ms = timed(lambda: pk.pc_frame_attn(Q48, K48, V48, Nk48, call_scale, O=O48), 2)
+        score48_ms = timed(lambda: pk.pc_score(Q48, K48, Nk48, call_scale, score=sc48, ws=ws_s48, q_rows=rows48), 3)
         out["compaction_f48_in_place"] = comp
         out["compaction_f48_in_place_batched"] = comp_b
         out["compaction_f48_in_place_two_streams"] = comp_p
@@ -308,13 +323,13 @@ def main() -> int:
                 segs = synth.segment_table(w48.n_text, w48.n_frame, n_past)
                 b = pk.segment_budgets(segs, pk.pc_budget(pk.PC_BUDGET_POW, w48.n_frame, n_past, 0.85, 512))
                 _, nkp = pk.pc_compact_plan(segs, b)
-                d_ms = timed(lambda: pk.pc_frame_attn(Q48, K48, V48, nk_f, w48.scale, O=O48), 2)
+                d_ms = timed(lambda: pk.pc_frame_attn(Q48, K48, V48, nk_f, call_scale, O=O48), 2)
 
                 def packed_path():
-                    pk.pc_score(Q48, K48, nk_f, w48.scale, score=sc48, ws=ws_s48, q_rows=rows48)
+                    pk.pc_score(Q48, K48, nk_f, call_scale, score=sc48, ws=ws_s48, q_rows=rows48)
                     pk.pc_compact(K48, V48, pos48, sc48, segs, b, out=(Kw, Vw, pw), ws=ws_c48)
                 p_path_ms = timed(packed_path, 2)
-                p_ms = timed(lambda: pk.pc_frame_attn(Q48, Kw, Vw, nkp, w48.scale, O=O48), 2)
+                p_ms = timed(lambda: pk.pc_frame_attn(Q48, Kw, Vw, nkp, call_scale, O=O48), 2)
                 table.append({"frame": f, "Nk_dense": nk_f, "Nk_packed": nkp, "dense_ms": round(d_ms, 4),
                               "packed_attn_ms": round(p_ms, 4), "score_compact_ms": round(p_path_ms, 4)})
             last4 = table[-4:]
@@ -344,9 +359,10 @@ def main() -> int:
         cap_dense = n_anchor + (F - 1) * n
         streams = [synth.DeviceRollingStream(1000 * (l + 1), hq5, hkv5, D, F, sections, dev) for l in range(L)]
         packed = [RollingLayer(hq5, hkv5, D, cap_packed, n, scale5, mode=args.rollout_mode, gamma=0.85, b_min=512,
-                               budget_tokens=tok_budget, n_score=512, sections=sections, device=dev)
+                               budget_tokens=tok_budget, n_score=512, sections=sections, device=dev, fold_scale=fold)
                   for _ in range(L)]
-        dense = [RollingLayer(hq5, hkv5, D, cap_dense, n, scale5, mode="dense", sections=sections, device=dev)
+        dense = [RollingLayer(hq5, hkv5, D, cap_dense, n, scale5, mode="dense", sections=sections, device=dev,
+                              fold_scale=fold)
                  for _ in range(L)]
         apos = up(synth.cache_positions(n_text, gh, gw, 0), bf=False)
         for l in range(L):               # prefill: anchors, rotated on insert
@@ -388,7 +404,7 @@ def main() -> int:
                     if args.rollout_passes == 1:
                         layers[l].step(Qs[l], O=O5, q_pos=fpos)
                     else:
-                        pk.pc_rope3d(Qs[l], fpos, sections, 10000.0)
+                        pk.pc_rope3d(Qs[l], fpos, sections, 10000.0, out_scale=layers[l].q_out_scale)
                         layers[l].attend(Qs[l], O=O5, lse=lse5)
                         layers[l].refresh(Qs[l], lse=lse5)
                         for _ in range(args.rollout_passes - 1):

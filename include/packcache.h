@@ -103,10 +103,19 @@ int pc_budget(int mode, int n_frame_tokens, int n_past, double gamma, int b_min,
  * section of width s is dims (2i, 2i+1) and turns by pos_axis * base^(-2i/s).  Angles are
  * formed in fp64, the rotation in fp32.  A rebase by (-dt, 0, 0) is the same call with
  * pos = (-dt, 0, 0): rotations compose.
- * Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE (sections, D > 256, stride), PC_ERR_HIP.
+ *   out_scale > 0: the rotated row is multiplied by it before the one rounding to dtype
+ *   (1.0: plain rotation).  Queries rotated with out_scale = PC_FOLDED_Q_SCALE(scale) carry
+ *   the softmax scale of Eq. 2 and the base-2 conversion with them; pc_score and
+ *   pc_frame_attn called with scale = PC_SCALE_FOLDED then compute the same softmax(scale *
+ *   Q K^T) with one vector instruction per product element fewer.
+ * Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE (sections, D > 256, stride, out_scale),
+ * PC_ERR_HIP.
  */
+#define PC_SCALE_FOLDED 0.693147180559945309f                 /* ln 2: the scale left after folding */
+#define PC_FOLDED_Q_SCALE(scale) ((scale) * 1.4426950408889634) /* scale * log2(e): goes into Q */
 int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride_h,
-              const int32_t* pos, int sec_t, int sec_h, int sec_w, double base, void* stream);
+              const int32_t* pos, int sec_t, int sec_h, int sec_w, double base, double out_scale,
+              void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * pc_rebase -- temporal rebase of cached keys when the sliding window advances (Sec. 3.4,
@@ -143,6 +152,9 @@ int pc_rebase(void* K, int dtype, int Hkv, int D, int64_t k_stride_h, int32_t* p
  *          (one extra QK^T pass).
  *   score  dev, fp32 [Hsel][Nk], head stride score_stride_h; Hsel = Hkv, or 1 when
  *          share_heads != 0 (mass summed over the KV heads as well).
+ *   scale  > 0, the softmax scale of Eq. 2 (1/sqrt(D)).  scale = PC_SCALE_FOLDED (ln 2) with
+ *          queries that carry scale * log2(e) (see pc_rope3d) is the same computation and takes
+ *          the bf16 kernels' shorter loop; lse stays the natural-log sum-exp of the logits.
  * Summation order is fixed (no atomics): results are bit-reproducible.
  * Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE, PC_ERR_UNSUPPORTED, PC_ERR_WORKSPACE,
  * PC_ERR_HIP.
@@ -280,6 +292,10 @@ int pc_mask_scores(float* score, int Hsel, int Nk, int64_t score_stride_h, const
  * is applied.  The same call serves the packed and the full ("dense") cache.
  *   Q  dev [Hq][Nq][D], K, V dev [Hkv][Nk][D], O dev [Hq][Nq][D] (dtype; bf16 is rounded
  *   to nearest even), lse dev or NULL fp32 [Hq][Nq] = ln sum_j exp(scale * q.k_j).
+ *   scale > 0.  scale = PC_SCALE_FOLDED with queries that carry scale * log2(e) (see
+ *   pc_rope3d) is the same computation on the bf16 kernel's shorter loop: the scores start
+ *   from minus the running reference inside the matrix product and the probability is a bare
+ *   exp2.
  *   ws  dev or NULL: optional.  With a workspace of pc_frame_attn_workspace_bytes (0 for most
  *   shapes) the bf16 kernel may cut the keys into shares when Hq * ceil(Nq / 256) work-groups
  *   would fill the chip badly, and merge the partial results; without it (or with one that is

@@ -13,7 +13,7 @@ __all__ = [
     "PC_F32", "PC_BF16", "PC_SEG_TEXT", "PC_SEG_COND", "PC_SEG_FRAME", "PC_SEG_SELF",
     "PC_BUDGET_POW", "PC_BUDGET_NORM", "PC_BUDGET_HALF", "PC_BUDGET_SLIDE", "PC_MAX_SEGMENTS",
     "PackCacheError", "lib", "lib_path", "pc_version", "pc_strerror", "pc_budget", "pc_rope3d", "pc_rebase",
-    "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact", "pc_compact_batch", "pc_compact_batch_workspace_bytes", "PC_COMPACT_SELECT", "PC_COMPACT_GATHER", "pc_masked_budgets", "pc_mask_scores", "pc_compact_status",
+    "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact", "pc_compact_batch", "pc_compact_batch_workspace_bytes", "PC_COMPACT_SELECT", "PC_COMPACT_GATHER", "PC_SCALE_FOLDED", "folded_q_scale", "pc_masked_budgets", "pc_mask_scores", "pc_compact_status",
     "pc_compact_workspace_bytes", "pc_compact_prepared", "pc_frame_attn", "pc_frame_attn_workspace_bytes",
     "segment_budgets",
 ]
@@ -22,6 +22,14 @@ PC_F32, PC_BF16 = 0, 1
 PC_SEG_TEXT, PC_SEG_COND, PC_SEG_FRAME, PC_SEG_SELF = 0, 1, 2, 3
 PC_BUDGET_POW, PC_BUDGET_NORM, PC_BUDGET_HALF, PC_BUDGET_SLIDE = 0, 1, 2, 3
 PC_COMPACT_SELECT, PC_COMPACT_GATHER = 1, 2
+PC_SCALE_FOLDED = 0.6931471805599453      # ln 2: the scale to pass when Q carries folded_q_scale(scale)
+
+
+def folded_q_scale(scale: float) -> float:
+    """scale * log2(e): multiplied into the queries (pc_rope3d's out_scale), it leaves ln 2 as the
+    scale of pc_score / pc_frame_attn, which then run their shorter loops."""
+    return float(scale) * 1.4426950408889634
+
 PC_MAX_SEGMENTS = 120
 
 _LIB = None
@@ -59,7 +67,7 @@ def lib() -> C.CDLL:
         L.pc_version.restype = C.c_int
         L.pc_budget.argtypes = [C.c_int, C.c_int, C.c_int, C.c_double, C.c_int, i32p]
         L.pc_rope3d.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, i64, vp, C.c_int, C.c_int, C.c_int,
-                                C.c_double, vp]
+                                C.c_double, C.c_double, vp]
         L.pc_rebase.argtypes = [vp, C.c_int, C.c_int, C.c_int, i64, vp, C.c_int, i64, C.c_int, C.c_int, C.c_int,
                                 C.c_int, C.c_int, C.c_int, C.c_double, vp]
         L.pc_score_workspace_bytes.restype = sz
@@ -152,12 +160,15 @@ def segment_budgets(segments: Sequence[Sequence[int]], by_distance: Sequence[int
     return out
 
 
-def pc_rope3d(x, pos, sections: Sequence[int], base: float = 10000.0) -> None:
-    """x [H][n][D] (bf16/fp32, device) rotated in place by pos int32 [n][3]."""
+def pc_rope3d(x, pos, sections: Sequence[int], base: float = 10000.0, out_scale: float = 1.0) -> None:
+    """x [H][n][D] (bf16/fp32, device) rotated in place by pos int32 [n][3] and multiplied by
+    out_scale before the one rounding (folded_q_scale(scale) for queries that go to pc_score /
+    pc_frame_attn with scale = PC_SCALE_FOLDED)."""
     H, n, D = x.shape
     _rows_dense(x, "x")
     _check(lib().pc_rope3d(x.data_ptr(), _dtype_code(x), H, n, D, x.stride(0), pos.data_ptr(),
-                           int(sections[0]), int(sections[1]), int(sections[2]), float(base), _stream()))
+                           int(sections[0]), int(sections[1]), int(sections[2]), float(base), float(out_scale),
+                           _stream()))
 
 
 def pc_rebase(K, pos, row0: int, n_rows: int, delta_t: int, sections: Sequence[int], base: float = 10000.0) -> None:

@@ -12,6 +12,8 @@
 //     the products of the neighbouring half tiles.  No row maximum is taken on the fast path:
 //     probabilities are formed against the standing reference, and a half tile is redone
 //     (and the accumulators rescaled) only when one of its row sums runs away.
+//   * With scale = ln 2 (the caller multiplied Q by scale * log2(e), e.g. while rotating it)
+//     the affine step c*s - m is taken out of the loop: see kUnitC below.
 // fp32 tier (D = 64 or 128): one query row per thread, plain FMA; the correctness tier.
 #include <math.h>
 
@@ -63,10 +65,16 @@ __device__ __forceinline__ void stage_tile(const uint16_t* __restrict__ base_h, 
 // taken on the fast path.  If any row sum of the half tile comes out above kRescaleTrigger
 // (a score outgrew the reference: rare, at most once per 2^10 of growth), the half tile is
 // redone against its exact maximum and O, l are rescaled.
+// kUnitC: the caller folded scale * log2(e) into Q (c == 1).  The score products then start
+// from -m_ref instead of zero (neg_m: the reference in all 16 accumulator registers of the
+// lane, which holds one query), so a score arrives as s - m_ref and the probability is a bare
+// exp2: one vector instruction per element fewer.  When the reference moves, the scores that
+// were started from the old one are shifted by the difference.
+template <bool kUnitC>
 __device__ __forceinline__ void pipeline_phase(
     const lds_u8* k_half, const int (&k_off)[8], const lds_u8* v_half, const int (&v_off)[4],
     const bf16x8 (&qf)[8], f32x16& s_nxt, const bf16x8 (&p_mm)[2], f32x16 (&o)[4], const f32x16& s_cur,
-    bf16x8 (&p_cur)[2], float& m_ref, float& l_run, float c) {
+    bf16x8 (&p_cur)[2], float& m_ref, float& l_run, float c, f32x16& neg_m) {
   // fragment k: 0..7 -> K rows, contraction step k; 8..15 -> V^T (key step (k-8)/4, block (k-8)%4)
   auto frag = [&](int k) -> bf16x8 {
     if (k < 8) {
@@ -100,13 +108,13 @@ __device__ __forceinline__ void pipeline_phase(
   for (int k = 0; k < 16; ++k) {
     const bf16x8 f = ring[k % kRing];
     if (k < 8) {
-      s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[k], k == 0 ? zero : s_acc, 0, 0, 0);
+      s_acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, qf[k], k == 0 ? (kUnitC ? neg_m : zero) : s_acc, 0, 0, 0);
     } else {
       const int ks = (k - 8) >> 2, db = (k - 8) & 3;
       o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, p_mm[ks], o[db], 0, 0, 0);
     }
     if (k + kRing < 16) ring[k % kRing] = frag(k + kRing);
-    pv[k] = __builtin_amdgcn_exp2f(fmaf(s_cur[k], c, -m_ref));
+    pv[k] = kUnitC ? __builtin_amdgcn_exp2f(s_cur[k]) : __builtin_amdgcn_exp2f(fmaf(s_cur[k], c, -m_ref));
     psum += pv[k];
     if (k & 1) {
       p_cur[k >> 3][(k & 7) - 1] = static_cast<__bf16>(pv[k - 1]);
@@ -122,13 +130,21 @@ __device__ __forceinline__ void pipeline_phase(
     float mx = s_cur[0];
 #pragma unroll
     for (int i = 1; i < 16; ++i) mx = fmaxf(mx, s_cur[i]);
-    const float m_new = fmaxf(m_ref, wave_half_max(mx) * c);
+    // unit c: s_cur already holds s - m_ref, so the new reference lies max(0, max s_cur) above the old one
+    const float m_new = kUnitC ? m_ref + fmaxf(0.f, wave_half_max(mx)) : fmaxf(m_ref, wave_half_max(mx) * c);
     const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);
     psum = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      pv[i] = __builtin_amdgcn_exp2f(fmaf(s_cur[i], c, -m_new));
+      pv[i] = kUnitC ? __builtin_amdgcn_exp2f(s_cur[i] - (m_new - m_ref)) : __builtin_amdgcn_exp2f(fmaf(s_cur[i], c, -m_new));
       psum += pv[i];
+    }
+    if constexpr (kUnitC) {   // the scores just formed were started from the old reference
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        s_acc[i] -= m_new - m_ref;
+        neg_m[i] = -m_new;
+      }
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) p_cur[i >> 3][i & 7] = static_cast<__bf16>(pv[i]);
@@ -157,6 +173,7 @@ __device__ __forceinline__ void pipeline_phase(
 // straight into the LDS slots just released (four slots per operand, 128 KB), three tiles
 // ahead of their first use.
 // ------------------------------------------------------------------------------------------
+template <bool kUnitC>
 __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     uint16_t* __restrict__ O, float* __restrict__ lse, int rep, int Nq, int Nk, int64_t q_stride_h,
@@ -210,6 +227,9 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
       pB[ks][e] = static_cast<__bf16>(0.f);
     }
   float m_ref = -INFINITY, l_run = 0.f;
+  f32x16 neg_m;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) neg_m[i] = 0.f;
 
   // per-lane byte offsets inside a half tile
   int k_off[8];  // K fragment of contraction step s: row l32, chunk 2s+g
@@ -270,6 +290,13 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
 #pragma unroll
     for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sA[i]);
     m_ref = wave_half_max(mx) * c;
+    if constexpr (kUnitC) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        sA[i] -= m_ref;
+        neg_m[i] = -m_ref;
+      }
+    }
     if (tail && n == 1) mask_tail(sA, lim_a);
   }
 
@@ -283,8 +310,8 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     const bool last = j + 1 == n;
     // ---- phase 1: S_B(j), O += V_B(j-1) P_B(j-1)  |  P_A(j) ----
     if (active) {
-      pipeline_phase(smem + k_cur + 32 * kRowBytes, k_off, smem + v_prev + 32 * kRowBytes, v_off, qf, sB, pB, o, sA,
-                     pA, m_ref, l_run, c);
+      pipeline_phase<kUnitC>(smem + k_cur + 32 * kRowBytes, k_off, smem + v_prev + 32 * kRowBytes, v_off, qf, sB, pB, o, sA,
+                     pA, m_ref, l_run, c, neg_m);
       if (last && tail) mask_tail(sB, lim_b);
     }
     // One barrier per tile: every wave is past K(j) and V(j-1), and K(j+1), V(j) (fetched
@@ -296,7 +323,7 @@ __global__ __launch_bounds__(kPPThreads, 1) void attn_bf16_kernel(
     // ---- phase 2: S_A(j+1), O += V_A(j) P_A(j)  |  P_B(j) ----
     // (after the last tile S_A is formed from a clamped tile and never used)
     if (active) {
-      pipeline_phase(smem + k_nxt, k_off, smem + v_cur, v_off, qf, sA, pA, o, sB, pB, m_ref, l_run, c);
+      pipeline_phase<kUnitC>(smem + k_nxt, k_off, smem + v_cur, v_off, qf, sA, pA, o, sB, pB, m_ref, l_run, c, neg_m);
       if (j + 2 == n && tail) mask_tail(sA, lim_a);
     }
   };
@@ -526,8 +553,10 @@ extern "C" int pc_frame_attn(const void* Q, const void* K, const void* V, int dt
                          reinterpret_cast<uintptr_t>(V) | reinterpret_cast<uintptr_t>(O);
     PC_REQUIRE(al % 16 == 0 && q_stride_h % 8 == 0 && kv_stride_h % 8 == 0 && o_stride_h % 8 == 0,
                PC_ERR_SHAPE, "pc_frame_attn: bf16 tensors and head strides must be 16-byte aligned");
-    static std::atomic<uint64_t> lds_ok{0};
-    if (int rc = allow_dynamic_lds(reinterpret_cast<const void*>(attn_bf16_kernel), kSmemBytes, lds_ok, "pc_frame_attn"))
+    const bool unit_c = scale * 1.4426950408889634f == 1.0f;
+    static std::atomic<uint64_t> lds_ok{0}, lds_ok_u{0};
+    if (int rc = unit_c ? allow_dynamic_lds(reinterpret_cast<const void*>(attn_bf16_kernel<true>), kSmemBytes, lds_ok_u, "pc_frame_attn")
+                        : allow_dynamic_lds(reinterpret_cast<const void*>(attn_bf16_kernel<false>), kSmemBytes, lds_ok, "pc_frame_attn"))
       return rc;
     const int n_tiles_q = ceil_div(Nq, kBM);
     const float c = scale * 1.4426950408889634f;
@@ -543,7 +572,7 @@ extern "C" int pc_frame_attn(const void* Q, const void* K, const void* V, int dt
       part_ml = reinterpret_cast<float2*>(static_cast<uint8_t*>(ws) +
                                           align_up(static_cast<size_t>(n_splits) * Hq * Nq * kD * sizeof(float), 256));
     }
-    attn_bf16_kernel<<<dim3(n_tiles_q * Hq * n_splits), kPPThreads, kSmemBytes, s>>>(
+    (unit_c ? attn_bf16_kernel<true> : attn_bf16_kernel<false>)<<<dim3(n_tiles_q * Hq * n_splits), kPPThreads, kSmemBytes, s>>>(
         static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
         static_cast<const uint16_t*>(V), static_cast<uint16_t*>(O), lse, rep, Nq, Nk, q_stride_h,
         kv_stride_h, o_stride_h, c, n_tiles_q, n_splits, part_o, part_ml);

@@ -24,7 +24,7 @@ template <typename T>
 __global__ __launch_bounds__(kThreads) void rope3d_kernel(T* __restrict__ x, int H, int n, int D,
                                                           int64_t stride_h,
                                                           const int32_t* __restrict__ pos,
-                                                          RopeFreq fr) {
+                                                          RopeFreq fr, double out_scale) {
   __shared__ float2 cs[kTokPerBlock][kMaxPairs];
   const int tok0 = blockIdx.x * kTokPerBlock;
   const int pairs = D / 2;
@@ -37,7 +37,8 @@ __global__ __launch_bounds__(kThreads) void rope3d_kernel(T* __restrict__ x, int
                          fr.inv_freq[p];
       double s, c;
       sincos(ang, &s, &c);
-      v = make_float2(static_cast<float>(c), static_cast<float>(s));
+      // the output scale rides on the rotation: no instruction per element, one rounding of the result
+      v = make_float2(static_cast<float>(c * out_scale), static_cast<float>(s * out_scale));
     }
     cs[t][p] = v;
   }
@@ -133,7 +134,7 @@ using namespace pc;
 
 extern "C" int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride_h,
                          const int32_t* pos, int sec_t, int sec_h, int sec_w, double base,
-                         void* stream) {
+                         double out_scale, void* stream) {
   PC_REQUIRE(dtype == PC_F32 || dtype == PC_BF16, PC_ERR_DTYPE, "pc_rope3d: dtype %d", dtype);
   PC_REQUIRE(H >= 0 && n >= 0 && D > 0, PC_ERR_SHAPE, "pc_rope3d: H=%d n=%d D=%d", H, n, D);
   const int secs[3] = {sec_t, sec_h, sec_w};
@@ -145,6 +146,7 @@ extern "C" int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride
   PC_REQUIRE(D <= 2 * kMaxPairs && D % 8 == 0, PC_ERR_SHAPE,
              "pc_rope3d: D=%d must be a multiple of 8 and <= %d", D, 2 * kMaxPairs);
   PC_REQUIRE(base > 0.0, PC_ERR_SHAPE, "pc_rope3d: base %g", base);
+  PC_REQUIRE(out_scale > 0.0 && isfinite(out_scale), PC_ERR_SHAPE, "pc_rope3d: out_scale %g must be > 0", out_scale);
   if (H == 0 || n == 0) return PC_OK;
   PC_REQUIRE(x && pos, PC_ERR_NULL, "pc_rope3d: x or pos is NULL");
   PC_REQUIRE(stride_h >= static_cast<int64_t>(n) * D || H == 1, PC_ERR_SHAPE,
@@ -169,9 +171,9 @@ extern "C" int pc_rope3d(void* x, int dtype, int H, int n, int D, int64_t stride
   const dim3 grid(ceil_div(n, kTokPerBlock), H >= 8 ? 2 : 1);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (dtype == PC_BF16)
-    rope3d_kernel<uint16_t><<<grid, kThreads, 0, s>>>(static_cast<uint16_t*>(x), H, n, D, stride_h, pos, fr);
+    rope3d_kernel<uint16_t><<<grid, kThreads, 0, s>>>(static_cast<uint16_t*>(x), H, n, D, stride_h, pos, fr, out_scale);
   else
-    rope3d_kernel<float><<<grid, kThreads, 0, s>>>(static_cast<float*>(x), H, n, D, stride_h, pos, fr);
+    rope3d_kernel<float><<<grid, kThreads, 0, s>>>(static_cast<float*>(x), H, n, D, stride_h, pos, fr, out_scale);
   PC_CHECK_LAUNCH("pc_rope3d");
   return PC_OK;
 }

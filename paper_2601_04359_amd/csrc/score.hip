@@ -9,7 +9,9 @@
 //   2. column pass: p = exp2(c*s - lse2) with the FINAL normaliser, un-rounded, in fp32,
 //                   summed down the query axis (queries split over work-groups, partial
 //                   sums added in a fixed order).
-// A caller that already has the log-sum-exp skips pass 1.
+// A caller that already has the log-sum-exp skips pass 1.  With scale = ln 2 (the caller folded
+// scale * log2(e) into the queries, c == 1) the products of pass 2 start from minus the
+// normaliser instead of zero, so an element arrives as s - lse2 and costs a bare exp2.
 //
 // Both passes have the same shape.  One operand is stationary: every wave keeps 64 of its
 // rows as MFMA fragments in registers for the whole kernel (queries in pass 1, keys in
@@ -60,11 +62,12 @@ __device__ __forceinline__ void stage_rows(Src&& src, uint32_t lds_tile, int wav
   }
 }
 
-// acc[b] = (32 streamed rows at `half`) x (stationary block b)^T, 16 products; after each
-// product epi(i) runs one sixteenth of the vector work of the previous half tile.
-template <class Epi>
+// acc[b] = init(b) + (32 streamed rows at `half`) x (stationary block b)^T, 16 products; after
+// each product epi(i) runs one sixteenth of the vector work of the previous half tile.
+// kInit = false: the products start from zero and init is not called.
+template <bool kInit, class Init, class Epi>
 __device__ __forceinline__ void stream_phase(const lds_u8* half, const int (&a_off)[8],
-                                             const bf16x8 (&st)[2][8], f32x16 (&acc)[2], Epi&& epi) {
+                                             const bf16x8 (&st)[2][8], f32x16 (&acc)[2], Init&& init, Epi&& epi) {
   bf16x8 ring[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) ring[r] = lds_frag(half + a_off[r]);
@@ -77,7 +80,10 @@ __device__ __forceinline__ void stream_phase(const lds_u8* half, const int (&a_o
     if (s + 4 < 8) ring[s & 3] = lds_frag(half + a_off[s + 4]);
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-      acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st[b][s], s == 0 ? zero : acc[b], 0, 0, 0);
+      if constexpr (kInit)
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st[b][s], s == 0 ? init(b) : acc[b], 0, 0, 0);
+      else
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st[b][s], s == 0 ? zero : acc[b], 0, 0, 0);
       epi(s * 2 + b);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -90,6 +96,9 @@ __device__ __forceinline__ void stream_phase(const lds_u8* half, const int (&a_o
 // halves of the wave are merged once at the end.
 struct RowState {
   float m[2], l[2];
+};
+struct NoInit {
+  __device__ const f32x16& operator()(int) const { __builtin_unreachable(); }
 };
 constexpr float kRowTrigger = 1024.f;  // phase sum that forces a new reference maximum
 
@@ -200,7 +209,7 @@ __global__ __launch_bounds__(kThreads, 1) void score_rowpass_bf16(
   stage(2);
   asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
   __syncthreads();
-  stream_phase(slot(0), a_off, qf, sA, [](int) {});
+  stream_phase<false>(slot(0), a_off, qf, sA, NoInit{}, [](int) {});
   // Tile j lives in LDS slot j % 4; the loop is unrolled over the slots so that their bases are
   // immediates of the LDS reads.
   auto tile_body = [&](int j, auto slot_tag) {
@@ -210,12 +219,13 @@ __global__ __launch_bounds__(kThreads, 1) void score_rowpass_bf16(
     __syncthreads();  // tile j+1 has landed everywhere; slot of tile j-1 is free
     stage(j + 3);
     if (tail) mask_keys(sA, (t_begin + j) * kTileRows, Nk, g);
-    stream_phase(smem + u * kTileBytes + 32 * kRowBytes, a_off, qf, sB,
-                 [&](int i) { row_epilogue(i, sA, st, psum, c); });
+    stream_phase<false>(smem + u * kTileBytes + 32 * kRowBytes, a_off, qf, sB, NoInit{},
+                        [&](int i) { row_epilogue(i, sA, st, psum, c); });
     row_commit(sA, st, psum, c);
     if (tail) mask_keys(sB, (t_begin + j) * kTileRows + 32, Nk, g);
     if (j + 1 < n) {
-      stream_phase(smem + ((u + 1) & 3) * kTileBytes, a_off, qf, sA, [&](int i) { row_epilogue(i, sB, st, psum, c); });
+      stream_phase<false>(smem + ((u + 1) & 3) * kTileBytes, a_off, qf, sA, NoInit{},
+                          [&](int i) { row_epilogue(i, sB, st, psum, c); });
     } else {
 #pragma unroll
       for (int i = 0; i < 16; ++i) row_epilogue(i, sB, st, psum, c);
@@ -243,16 +253,16 @@ __global__ __launch_bounds__(kThreads, 1) void score_rowpass_bf16(
   }
 }
 
-// Merge the per-split (max, sum) pairs in split order: lse2 = log2 sum_j 2^(c * s_j).  The
-// result is laid out [head][n_pad] with n_pad a multiple of the streamed tile; the padding
-// rows hold +inf so that they add nothing in pass 2.
+// Merge the per-split (max, sum) pairs in split order: lse2 = log2 sum_j 2^(c * s_j), stored
+// NEGATED (pass 2 adds it).  The result is laid out [head][n_pad] with n_pad a multiple of the
+// streamed tile; the padding rows hold -inf so that they add nothing in pass 2.
 __global__ void score_merge_rows(const float2* __restrict__ part, float* __restrict__ lse2, int Hq, int n_qs,
                                  int n_pad, int n_splits) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= Hq * n_pad) return;
   const int h = r / n_pad, row = r % n_pad;
   if (row >= n_qs) {
-    lse2[r] = INFINITY;
+    lse2[r] = -INFINITY;
     return;
   }
   const int64_t n_rows = static_cast<int64_t>(Hq) * n_qs, at = static_cast<int64_t>(h) * n_qs + row;
@@ -266,31 +276,41 @@ __global__ void score_merge_rows(const float2* __restrict__ part, float* __restr
 #pragma unroll
   for (int s = 0; s < kMaxSplits; ++s)
     if (p[s].y > 0.f) l += p[s].y * exp2f(p[s].x - m);
-  lse2[r] = m + log2f(l);
+  lse2[r] = -(m + log2f(l));
 }
 
 // A caller's natural-log LSE, indexed like the rows of Qs, -> the dense [head][n_pad] layout
-// of pass 2 (times `mul`: log2(e) for the base-2 kernels); padding rows get +inf.
+// of pass 2 (times `mul`: -log2(e) for the base-2 kernels, which add the negated normaliser);
+// padding rows get `pad`.
 __global__ void score_import_lse(const float* __restrict__ lse, int64_t lse_stride_h,
                                  const int32_t* __restrict__ q_rows, float* __restrict__ out, int Hq, int n_qs,
-                                 int n_pad, float mul) {
+                                 int n_pad, float mul, float pad) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= Hq * n_pad) return;
   const int h = r / n_pad, row = r % n_pad;
-  out[r] = row < n_qs ? lse[h * lse_stride_h + (q_rows ? q_rows[row] : row)] * mul : INFINITY;
+  out[r] = row < n_qs ? lse[h * lse_stride_h + (q_rows ? q_rows[row] : row)] * mul : pad;
 }
 
 // ---- pass 2: column mass --------------------------------------------------------------------
 // S = Q K^T: a lane owns one key column of each stationary block and 16 of the 32 query rows
 // of the half tile.  The streamed operand is the list of (query head of the group, 64-row
 // tile) pairs; the normalisers of a tile travel through LDS beside it.
-__device__ __forceinline__ void col_epilogue(int i, const f32x16 (&s)[2], const float (&lq)[16], float (&colsum)[2],
+// nlq: the negated normalisers of the 16 query rows the lane holds.  kUnitC (c == 1): the
+// products were started from nlq, so s already holds s - lse2.
+template <bool kUnitC>
+__device__ __forceinline__ void col_epilogue(int i, const f32x16 (&s)[2], const f32x16& nlq, float (&colsum)[2],
                                              float c) {
   const int b = i >> 3, e = (i & 7) * 2;
-  colsum[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e], c, -lq[e]));
-  colsum[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e + 1], c, -lq[e + 1]));
+  if constexpr (kUnitC) {
+    colsum[b] += __builtin_amdgcn_exp2f(s[b][e]);
+    colsum[b] += __builtin_amdgcn_exp2f(s[b][e + 1]);
+  } else {
+    colsum[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e], c, nlq[e]));
+    colsum[b] += __builtin_amdgcn_exp2f(fmaf(s[b][e + 1], c, nlq[e + 1]));
+  }
 }
 
+template <bool kUnitC>
 __global__ __launch_bounds__(kThreads, 1) void score_colpass_bf16(
     const uint16_t* __restrict__ Qs, const int32_t* __restrict__ q_rows, const uint16_t* __restrict__ K,
     const float* __restrict__ lse2, float* __restrict__ out, int64_t out_stride_h, int64_t out_stride_split,
@@ -356,7 +376,7 @@ __global__ __launch_bounds__(kThreads, 1) void score_colpass_bf16(
     };
     auto slot = [&](int j) { return smem + (j & (kStages - 1)) * kTileBytes; };
     // normalisers of the 16 rows this lane holds in half `half` of tile j
-    auto load_lq = [&](int j, int half, float (&lq)[16]) {
+    auto load_lq = [&](int j, int half, f32x16& lq) {
       const lds_u8* base = smem + kLse0 + (j & (kStages - 1)) * kLseSlotBytes + (half * 32 + g * 4) * 4;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
@@ -367,7 +387,10 @@ __global__ __launch_bounds__(kThreads, 1) void score_colpass_bf16(
     };
 
     f32x16 sA[2], sB[2];
-    float lq[16];
+    f32x16 lq;            // general path: normalisers of the half tile whose elements the epilogue takes
+    f32x16 initA, initB;  // kUnitC: start values of the next sA / sB products, fetched one phase ahead
+    auto startA = [&](int) -> const f32x16& { return initA; };
+    auto startB = [&](int) -> const f32x16& { return initB; };
     int rows[2];
     src_rows(0, rows);
     stage(0, rows);
@@ -378,22 +401,27 @@ __global__ __launch_bounds__(kThreads, 1) void score_colpass_bf16(
     src_rows(3, rows);
     asm volatile("s_waitcnt vmcnt(4)" ::: "memory");  // at least the first tile's pieces
     __syncthreads();
-    stream_phase(slot(0), a_off, kf, sA, [](int) {});
+    if constexpr (kUnitC) {
+      load_lq(0, 0, initA);
+      load_lq(0, 1, initB);
+    }
+    stream_phase<kUnitC>(slot(0), a_off, kf, sA, startA, [](int) {});
     auto tile_body = [&](int j, auto slot_tag) {  // slot j % 4 as a compile-time constant, as in pass 1
       constexpr int u = decltype(slot_tag)::value;
       dma_wait_all_but_newest();
       __syncthreads();  // tile j+1 has landed everywhere; slot of tile j-1 is free
       stage(j + 3, rows);
       src_rows(j + 4, rows);
-      load_lq(u, 0, lq);
-      stream_phase(smem + u * kTileBytes + 32 * kRowBytes, a_off, kf, sB,
-                   [&](int i) { col_epilogue(i, sA, lq, colsum, c); });
-      load_lq(u, 1, lq);
+      if constexpr (kUnitC) load_lq((u + 1) & 3, 0, initA); else load_lq(u, 0, lq);
+      stream_phase<kUnitC>(smem + u * kTileBytes + 32 * kRowBytes, a_off, kf, sB, startB,
+                           [&](int i) { col_epilogue<kUnitC>(i, sA, lq, colsum, c); });
+      if constexpr (kUnitC) load_lq((u + 1) & 3, 1, initB); else load_lq(u, 1, lq);
       if (j + 1 < n) {
-        stream_phase(smem + ((u + 1) & 3) * kTileBytes, a_off, kf, sA, [&](int i) { col_epilogue(i, sB, lq, colsum, c); });
+        stream_phase<kUnitC>(smem + ((u + 1) & 3) * kTileBytes, a_off, kf, sA, startA,
+                             [&](int i) { col_epilogue<kUnitC>(i, sB, lq, colsum, c); });
       } else {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) col_epilogue(i, sB, lq, colsum, c);
+        for (int i = 0; i < 16; ++i) col_epilogue<kUnitC>(i, sB, lq, colsum, c);
       }
     };
     for (int j0 = 0; j0 < n; j0 += kStages) {
@@ -606,12 +634,17 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
     const uintptr_t al = reinterpret_cast<uintptr_t>(Qs) | reinterpret_cast<uintptr_t>(K);
     PC_REQUIRE(al % 16 == 0 && q_stride_h % 8 == 0 && k_stride_h % 8 == 0, PC_ERR_SHAPE,
                "pc_score: bf16 tensors and head strides must be 16-byte aligned");
-    static std::atomic<uint64_t> row_ok{0}, col_ok{0};
+    const float c = scale * 1.4426950408889634f;
+    // c == 1 (scale = ln 2): the caller folded the softmax scale and log2(e) into the queries, and
+    // the column pass takes the affine step out of its loop (the row pass has no registers left
+    // for the start values of its products and would gain nothing from rebuilding them per phase)
+    const bool unit_c = c == 1.0f;
+    const auto col_kernel = unit_c ? score_colpass_bf16<true> : score_colpass_bf16<false>;
+    static std::atomic<uint64_t> row_ok{0}, col_ok[2];
     if (int rc = allow_dynamic_lds(reinterpret_cast<const void*>(score_rowpass_bf16), kRowSmem, row_ok, "pc_score"))
       return rc;
-    if (int rc = allow_dynamic_lds(reinterpret_cast<const void*>(score_colpass_bf16), kColSmem, col_ok, "pc_score"))
+    if (int rc = allow_dynamic_lds(reinterpret_cast<const void*>(col_kernel), kColSmem, col_ok[unit_c], "pc_score"))
       return rc;
-    const float c = scale * 1.4426950408889634f;
     const int n_pad = padded_rows(n_qs);
     if (lse == nullptr) {
       const int n_row_tiles = ceil_div(n_qs, kBlockRows);
@@ -624,13 +657,13 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
       PC_CHECK_LAUNCH("pc_score merge");
     } else {
       score_import_lse<<<ceil_div(Hq * n_pad, 256), 256, 0, s>>>(lse, lse_stride_h, q_rows, ws_lse, Hq, n_qs, n_pad,
-                                                                 1.4426950408889634f);
+                                                                 -1.4426950408889634f, -INFINITY);
       PC_CHECK_LAUNCH("pc_score lse import");
     }
     const int n_key_blocks = ceil_div(Nk, kBlockRows);
     const int n_qsplits = choose_splits(n_key_blocks * Hkv, rep * (n_pad / kTileRows), kMaxQSplits);
     const bool direct = n_qsplits == 1 && !share_heads;
-    score_colpass_bf16<<<n_key_blocks * Hkv * n_qsplits, kThreads, kColSmem, s>>>(
+    col_kernel<<<n_key_blocks * Hkv * n_qsplits, kThreads, kColSmem, s>>>(
         static_cast<const uint16_t*>(Qs), q_rows, static_cast<const uint16_t*>(K), ws_lse, direct ? score : ws_col,
         direct ? score_stride_h : Nk, static_cast<int64_t>(Hkv) * Nk, Hkv, rep, n_qs, Nk, q_stride_h, k_stride_h, c,
         n_key_blocks, n_qsplits);
@@ -649,7 +682,8 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
     const float* k = static_cast<const float*>(K);
     const float* lse_in = ws_lse;
     if (lse != nullptr) {
-      score_import_lse<<<ceil_div(Hq * n_qs, 256), 256, 0, s>>>(lse, lse_stride_h, q_rows, ws_lse, Hq, n_qs, n_qs, 1.f);
+      score_import_lse<<<ceil_div(Hq * n_qs, 256), 256, 0, s>>>(lse, lse_stride_h, q_rows, ws_lse, Hq, n_qs, n_qs, 1.f,
+                                                                INFINITY);
       PC_CHECK_LAUNCH("pc_score lse import");
     } else {
       const dim3 grid(ceil_div(n_qs, 64), Hq);

@@ -37,12 +37,18 @@ class RollingLayer:
     def __init__(self, Hq: int, Hkv: int, D: int, capacity: int, n_frame: int, scale: float,
                  mode: str = "pow", gamma: float = 0.85, b_min: int = 512, budget_tokens: int | None = None,
                  n_score: int = 512, sections=(32, 48, 48), base: float = 10000.0, dtype=None, device="cuda:0",
-                 slide_t_scale: int | None = None, share_heads: bool = False):
+                 slide_t_scale: int | None = None, share_heads: bool = False, fold_scale: bool = False):
         import torch
         if mode not in MODES:
             raise ValueError(f"mode {mode!r} not in {sorted(MODES)}")
         self.Hq, self.Hkv, self.D, self.capacity, self.n_frame = Hq, Hkv, D, capacity, n_frame
         self.scale, self.mode, self.gamma, self.b_min = scale, mode, gamma, b_min
+        # fold_scale: the queries carry scale * log2(e) (step() multiplies it in while rotating; a
+        # caller that rotates them itself passes them that way) and the scoring and attention calls
+        # get ln 2 as their scale: the same softmax on the kernels' shorter loops
+        self.fold_scale = fold_scale
+        self.q_out_scale = pk.folded_q_scale(scale) if fold_scale else 1.0
+        self.call_scale = pk.PC_SCALE_FOLDED if fold_scale else scale
         # POW floors gamma^d of a whole frame; NORM / HALF / SLIDE split a fixed token budget
         self.budget_tokens = n_frame if budget_tokens is None else budget_tokens
         self.sections, self.base = tuple(sections), base
@@ -124,19 +130,19 @@ class RollingLayer:
         budgets = self.budgets()
         if all(b >= s[1] for s, b in zip(self.segments, budgets) if s[2] == pk.PC_SEG_FRAME):
             return   # every frame is within its budget: nothing to score, nothing to move
-        pk.pc_score(Q, self.K, self.nk, self.scale, lse=lse, score=self.score, share_heads=self.share_heads,
+        pk.pc_score(Q, self.K, self.nk, self.call_scale, lse=lse, score=self.score, share_heads=self.share_heads,
                     ws=self._ws_score, q_rows=self.q_rows)
         self.segments, self.nk = pk.pc_compact(self.K, self.V, self.pos, self.score, self.segments,
                                                budgets, share_heads=self.share_heads, ws=self._ws_compact)
 
     def attend(self, Q, O=None, lse=None):
         """The (rotated) queries Q over the cache as it stands -> O (and the log-sum-exp)."""
-        return pk.pc_frame_attn(Q, self.K, self.V, self.nk, self.scale, O=O, lse=lse, ws=self._ws_attn)
+        return pk.pc_frame_attn(Q, self.K, self.V, self.nk, self.call_scale, O=O, lse=lse, ws=self._ws_attn)
 
     def step(self, Q, O=None, q_pos=None, lse=None):
         """Queries Q [Hq][n_frame][D] of the frame being generated -> O.  q_pos (int32
-        [n_frame][3], device): rotate Q in place first."""
+        [n_frame][3], device): rotate Q in place first (with fold_scale, times scale * log2(e))."""
         if q_pos is not None:
-            pk.pc_rope3d(Q, q_pos, self.sections, self.base)
+            pk.pc_rope3d(Q, q_pos, self.sections, self.base, out_scale=self.q_out_scale)
         self.refresh(Q)
         return self.attend(Q, O=O, lse=lse)

@@ -91,6 +91,24 @@ def test_rope3d_parity(dtype, n, H):
         assert err.max() <= 2e-6
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rope3d_out_scale_is_applied_before_the_one_rounding(dtype):
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((3, 300, 128)).astype(np.float32)
+    if dtype == "bf16":
+        x = synth.to_bf16(x)
+    pos = np.stack([rng.integers(0, 450, 300), rng.integers(0, 380, 300), rng.integers(0, 670, 300)], 1).astype(np.int32)
+    s = pk.folded_q_scale(128 ** -0.5)
+    want = orc.rope3d(x, pos, (32, 48, 48), 1e4) * s
+    xd = dev(x, dtype)
+    pk.pc_rope3d(xd, dev(pos, None), (32, 48, 48), 1e4, out_scale=s)
+    got = host(xd).astype(np.float64)
+    tol = 2.0 ** -8 if dtype == "bf16" else 2e-6
+    assert np.all(np.abs(got - want) <= tol * np.abs(want) + 1e-6 * s)
+    if dtype == "bf16":     # one rounding, not two: most elements are the nearest bf16 of the exact value
+        assert (got == orc.round_to_bf16(want)).mean() > 0.99
+
+
 def test_rope3d_negative_shift_undoes_rotation_and_head_stride():
     # a rebase by (-dt, 0, 0) (Eq. 9) is a rotation with negative position; also exercises
     # a head stride larger than n*D (capacity > rows)
@@ -119,7 +137,16 @@ def _attn_case(dtype, hq, hkv, nq, nk, d, seed):
     return Q, K, V
 
 
-def _attn_check(dtype, Q, K, V, scale):
+def _fold(Q, scale):
+    """Queries that carry scale * log2(e) (rounded to bf16 once, as a rotation with out_scale
+    would leave them) and the scale that is left for the calls: the same softmax, and both
+    sides read the same bits."""
+    return synth.to_bf16((Q.astype(np.float64) * pk.folded_q_scale(scale)).astype(np.float32)), pk.PC_SCALE_FOLDED
+
+
+def _attn_check(dtype, Q, K, V, scale, fold=False):
+    if fold:
+        Q, scale = _fold(Q, scale)
     hq, nq, d = Q.shape
     nk = K.shape[1]
     lse = torch.empty((hq, nq), dtype=torch.float32, device=DEV)
@@ -136,23 +163,28 @@ def _attn_check(dtype, Q, K, V, scale):
     return err
 
 
+# fold = True: the queries carry scale * log2(e) and the calls get scale = ln 2 (the kernels'
+# shorter loop: scores start from minus the reference inside the matrix product)
+@pytest.mark.parametrize("fold", [False, True])
 @pytest.mark.parametrize("nq,nk", [(1, 1), (5, 63), (64, 64), (65, 65), (256, 128), (300, 777), (513, 1000)])
-def test_frame_attn_bf16_shapes(nq, nk):
+def test_frame_attn_bf16_shapes(nq, nk, fold):
     Q, K, V = _attn_case("bf16", 4, 2, nq, nk, 128, nq * 1000 + nk)
-    _attn_check("bf16", Q, K, V, 128 ** -0.5)
+    _attn_check("bf16", Q, K, V, 128 ** -0.5, fold)
 
 
-def test_frame_attn_bf16_gqa_groups_and_large_logits():
+@pytest.mark.parametrize("fold", [False, True])
+def test_frame_attn_bf16_gqa_groups_and_large_logits(fold):
     # 3 query heads per KV head; a strong shared direction makes logits reach ~ +-40
     Q, K, V = _attn_case("bf16", 6, 2, 130, 500, 128, 77)
     Q[..., :8] += 4.0
     K[:, ::7, :8] += 4.0
     Q, K = synth.to_bf16(Q), synth.to_bf16(K)
-    _attn_check("bf16", Q, K, V, 128 ** -0.5)
+    _attn_check("bf16", Q, K, V, 128 ** -0.5, fold)
 
 
+@pytest.mark.parametrize("fold", [False, True])
 @pytest.mark.parametrize("step", [0.05, 0.6, 40.0])
-def test_frame_attn_bf16_reference_maximum_is_refreshed(step):
+def test_frame_attn_bf16_reference_maximum_is_refreshed(step, fold):
     # logits that keep growing along the key axis: the kernel forms probabilities against a
     # reference maximum it only refreshes when a row sum runs away, so a slow drift (never
     # refreshed), a steady climb (refreshed every few tiles) and jumps of hundreds of units
@@ -166,19 +198,23 @@ def test_frame_attn_bf16_reference_maximum_is_refreshed(step):
     ramp = step * (np.arange(nk) // 32)                     # logit contribution grows per half tile
     K[..., 0] = (ramp / (8.0 * d ** -0.5))[None, :]
     Q, K, V = synth.to_bf16(Q), synth.to_bf16(K), synth.to_bf16(V)
-    _attn_check("bf16", Q, K, V, d ** -0.5)
+    _attn_check("bf16", Q, K, V, d ** -0.5, fold)
 
 
+@pytest.mark.parametrize("fold", [False, True])
 @pytest.mark.parametrize("hq,hkv,nq,nk", [(6, 2, 300, 3000), (24, 8, 520, 2100), (3, 1, 40, 5000)])
-def test_frame_attn_bf16_key_shares_and_merge(hq, hkv, nq, nk):
+def test_frame_attn_bf16_key_shares_and_merge(hq, hkv, nq, nk, fold):
     # shapes whose work-group count fills the chip badly: the keys are cut into shares and
     # merged (when a workspace is supplied); without one the un-split kernel must agree
     Q, K, V = _attn_case("bf16", hq, hkv, nq, nk, 128, 5)
     assert pk.pc_frame_attn_workspace_bytes(hq, nq, nk, 128) > 0
-    _attn_check("bf16", Q, K, V, 128 ** -0.5)                      # binding supplies the workspace
+    _attn_check("bf16", Q, K, V, 128 ** -0.5, fold)                # binding supplies the workspace
+    scale = 128 ** -0.5
+    if fold:
+        Q, scale = _fold(Q, scale)
     Qd, Kd, Vd = dev(Q, "bf16"), dev(K, "bf16"), dev(V, "bf16")
-    split = pk.pc_frame_attn(Qd, Kd, Vd, nk, 128 ** -0.5)
-    whole = pk.pc_frame_attn(Qd, Kd, Vd, nk, 128 ** -0.5, ws=torch.empty(16, dtype=torch.uint8, device=DEV))
+    split = pk.pc_frame_attn(Qd, Kd, Vd, nk, scale)
+    whole = pk.pc_frame_attn(Qd, Kd, Vd, nk, scale, ws=torch.empty(16, dtype=torch.uint8, device=DEV))
     assert (split.float() - whole.float()).abs().max().item() <= 2 ** -6   # two roundings of values of O(1)
 
 
@@ -211,10 +247,13 @@ def test_frame_attn_capacity_larger_than_rows():
 
 
 # ------------------------------------------------------------------------------- score
-def _score_check(w, Qs, K, share=False, lse=None):
+def _score_check(w, Qs, K, share=False, lse=None, fold=False):
     dt = w.dtype
-    got = host(pk.pc_score(dev(Qs, dt), dev(K, dt), K.shape[1], w.scale, lse=lse, share_heads=share)).astype(np.float64)
-    want = orc.score(Qs, K, w.scale, share_heads=share)
+    scale = w.scale
+    if fold:
+        Qs, scale = _fold(Qs, scale)
+    got = host(pk.pc_score(dev(Qs, dt), dev(K, dt), K.shape[1], scale, lse=lse, share_heads=share)).astype(np.float64)
+    want = orc.score(Qs, K, scale, share_heads=share)
     err = np.abs(got - want)
     # fp32 exponentials and sums of probabilities computed from exact bf16 products
     assert np.all(err <= 2e-7 + 2e-5 * want), (err.max(), (err / (want + 1e-30)).max())
@@ -228,25 +267,28 @@ def test_score_f32_config1():
     _score_check(w, w.Q, w.K)
 
 
+@pytest.mark.parametrize("fold", [False, True])
 @pytest.mark.parametrize("share", [False, True])
-def test_score_bf16_midsize(share):
+def test_score_bf16_midsize(share, fold):
     w = synth.midsize()
     Qs = w.Q[:, w.score_rows]
-    _score_check(w, Qs, w.K, share=share)
+    _score_check(w, Qs, w.K, share=share, fold=fold)
 
 
+@pytest.mark.parametrize("fold", [False, True])
 @pytest.mark.parametrize("n_qs,nk", [(1, 1), (33, 255), (64, 256), (65, 257), (130, 1300)])
-def test_score_bf16_ragged(n_qs, nk):
+def test_score_bf16_ragged(n_qs, nk, fold):
     w = synth.midsize(n_past=1)
     rng = np.random.default_rng(n_qs + nk)
     Qs = synth.to_bf16(rng.standard_normal((4, n_qs, 128)).astype(np.float32))
     K = synth.to_bf16(rng.standard_normal((2, nk, 128)).astype(np.float32))
     w.Hq, w.Hkv = 4, 2
-    _score_check(w, Qs, K)
+    _score_check(w, Qs, K, fold=fold)
 
 
+@pytest.mark.parametrize("fold", [False, True])
 @pytest.mark.parametrize("step", [0.05, 0.6, 40.0])
-def test_score_bf16_row_reference_is_refreshed(step):
+def test_score_bf16_row_reference_is_refreshed(step, fold):
     # the row pass sums exp2 against a standing reference and redoes a half tile only when a
     # partial sum runs away: logits drifting, climbing and jumping along the key axis
     rng = np.random.default_rng(4)
@@ -257,19 +299,24 @@ def test_score_bf16_row_reference_is_refreshed(step):
     Qs[..., 0] = 8.0
     K[..., 0] = (step * (np.arange(nk) // 32) / (8.0 * d ** -0.5))[None, :]
     Qs, K = synth.to_bf16(Qs), synth.to_bf16(K)
-    got = host(pk.pc_score(dev(Qs, "bf16"), dev(K, "bf16"), nk, d ** -0.5)).astype(np.float64)
-    want = orc.score(Qs, K, d ** -0.5)
+    scale = d ** -0.5
+    if fold:
+        Qs, scale = _fold(Qs, scale)
+    got = host(pk.pc_score(dev(Qs, "bf16"), dev(K, "bf16"), nk, scale)).astype(np.float64)
+    want = orc.score(Qs, K, scale)
     # fp32 exponents: a logit of magnitude L carries an absolute rounding error of about
     # L * 2^-23 in base-2 units twice over (the product c*s and the subtraction of the LSE)
     rel = max(2e-5, 4 * step * (nk // 32) * 1.4427 * 2.0 ** -23)
     assert np.all(np.abs(got - want) <= 2e-7 + rel * want), (np.abs(got - want) / (want + 1e-30)).max()
 
 
-def test_score_with_supplied_lse_matches_internal_pass():
+@pytest.mark.parametrize("fold", [False, True])
+def test_score_with_supplied_lse_matches_internal_pass(fold):
     w = synth.midsize()
     Qs = w.Q[:, w.score_rows]
-    _, L = orc.frame_attn(Qs, w.K, w.V, w.scale)
-    got, _ = _score_check(w, Qs, w.K, lse=dev(L.astype(np.float32), None))
+    Qo, scale = _fold(Qs, w.scale) if fold else (Qs, w.scale)
+    _, L = orc.frame_attn(Qo, w.K, w.V, scale)
+    got, _ = _score_check(w, Qs, w.K, lse=dev(L.astype(np.float32), None), fold=fold)
     assert got.shape == (w.Hkv, w.Nk)
 
 

@@ -17,11 +17,12 @@ from test_gpu_parity import DEV, dev, host
 pytestmark = pytest.mark.gpu
 
 
-def _rotated(case):
+def _rotated(case, q_scale=1.0):
     rnd = orc.round_to_bf16
     aK = rnd(orc.rope3d(case.anchor_K, case.anchor_pos, case.sections, case.base))
     frames = [(rnd(orc.rope3d(K, p, case.sections, case.base)), V, p) for K, V, p in case.frames]
-    queries = [rnd(orc.rope3d(Q, p, case.sections, case.base)) for Q, p in zip(case.queries, case.query_pos)]
+    queries = [rnd(orc.rope3d(Q, p, case.sections, case.base) * q_scale)
+               for Q, p in zip(case.queries, case.query_pos)]
     return aK, frames, queries
 
 
@@ -43,20 +44,22 @@ def _insert(layer, K, V, p, kind, frame):
     layer.commit(n, kind, frame)
 
 
-@pytest.mark.parametrize("mode,gamma,b_min,share", [
-    ("pow", 0.85, 32, False), ("pow", 0.6, 16, False), ("norm", 0.7, 20, False), ("half", 1.0, 30, False),
-    ("half", 1.0, 60, False), ("slide", 1.0, 0, False), ("dense", 1.0, 0, False), ("pow", 0.85, 32, True),
-    ("half", 1.0, 60, True)])
-def test_rolling_layer_matches_oracle(mode, gamma, b_min, share):
+# fold: the queries carry scale * log2(e) and the calls get ln 2 as their scale (the kernels' shorter loops)
+@pytest.mark.parametrize("mode,gamma,b_min,share,fold", [
+    ("pow", 0.85, 32, False, False), ("pow", 0.6, 16, False, False), ("norm", 0.7, 20, False, False),
+    ("half", 1.0, 30, False, False), ("half", 1.0, 60, False, False), ("slide", 1.0, 0, False, False),
+    ("dense", 1.0, 0, False, False), ("pow", 0.85, 32, True, False), ("half", 1.0, 60, True, False),
+    ("pow", 0.85, 32, False, True), ("norm", 0.7, 20, True, True), ("dense", 1.0, 0, False, True)])
+def test_rolling_layer_matches_oracle(mode, gamma, b_min, share, fold):
     case = synth.rolling_case(seed=11, n_steps=6)
-    aK, frames, queries = _rotated(case)
+    aK, frames, queries = _rotated(case, pk.folded_q_scale(case.scale) if fold else 1.0)
     want = orc.rolling_rollout(aK, case.anchor_V, case.anchor_pos, case.anchor_segments, frames, queries,
-                               case.scale, _budget_fn(mode, case, gamma, b_min), score_rows=case.score_rows,
-                               share_heads=share)
+                               pk.PC_SCALE_FOLDED if fold else case.scale, _budget_fn(mode, case, gamma, b_min),
+                               score_rows=case.score_rows, share_heads=share)
     n = case.n_frame
     layer = RollingLayer(case.Hq, case.Hkv, case.D, case.anchor_K.shape[1] + len(frames) * n, n, case.scale,
                          mode=mode, gamma=gamma, b_min=b_min, n_score=case.score_rows.size,
-                         sections=case.sections, base=case.base, device=DEV, share_heads=share)
+                         sections=case.sections, base=case.base, device=DEV, share_heads=share, fold_scale=fold)
     assert np.array_equal(host(layer.q_rows), case.score_rows)
     for (start, length, kind, frame) in case.anchor_segments:
         _insert(layer, aK[:, start:start + length], case.anchor_V[:, start:start + length],

@@ -112,8 +112,9 @@ def test_argument_validation_returns_before_any_device_work(L):
     # stride too small
     assert L.pc_frame_attn(one, one, one, 1, 2, 1, 4, 4, 128, 8, 512, 512, 0.1, one, None, None, 0, None) == -2
     # rope: sections must add up to D
-    assert L.pc_rope3d(one, 1, 1, 4, 128, 512, one, 32, 48, 40, 1e4, None) == -2
-    assert L.pc_rope3d(None, 1, 1, 4, 128, 512, one, 32, 48, 48, 1e4, None) == -1
+    assert L.pc_rope3d(one, 1, 1, 4, 128, 512, one, 32, 48, 40, 1e4, 1.0, None) == -2
+    assert L.pc_rope3d(one, 1, 1, 4, 128, 512, one, 32, 48, 48, 1e4, 0.0, None) == -2      # out_scale must be > 0
+    assert L.pc_rope3d(None, 1, 1, 4, 128, 512, one, 32, 48, 48, 1e4, 1.0, None) == -1
     # rebase: sections must add up to D; a temporal section that is not whole 16-byte chunks; NULL
     assert L.pc_rebase(one, 1, 1, 128, 512, one, 1, 12, 0, 4, 4, 32, 48, 40, 1e4, None) == -2
     assert L.pc_rebase(one, 1, 1, 128, 512, one, 1, 12, 0, 4, 4, 20, 60, 48, 1e4, None) == -4
