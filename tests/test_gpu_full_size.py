@@ -37,9 +37,14 @@ def _budgets(w, gamma):
     return pk.segment_budgets(w.segments, b)
 
 
+# fold = True is the form bench.py times: the query rotation multiplies scale * log2(e) into Q
+# and the scoring and attention calls get scale = ln 2
+@pytest.mark.parametrize("fold", [False, True])
 @pytest.mark.parametrize("frame", [2, 12, 24, 48])
-def test_full_size_frame(frame):
+def test_full_size_frame(frame, fold):
     w = synth.config2(seed=1000, n_past=frame - 1)
+    q_scale = pk.folded_q_scale(w.scale) if fold else 1.0
+    scale = pk.PC_SCALE_FOLDED if fold else w.scale
     Hq, Hkv, Nk, Nq = w.Hq, w.Hkv, w.Nk, w.Nq
     newest = w.segments[-1]
     a, n_new = newest[0], newest[1]
@@ -47,13 +52,13 @@ def test_full_size_frame(frame):
 
     # ---- a1: rotation of the new frame's queries and of the newest cached frame's keys
     Qd, Kd = dev(w.Q, "bf16"), dev(w.K, "bf16")
-    pk.pc_rope3d(Qd, dev(w.pos_q, None), w.sections, w.base)
+    pk.pc_rope3d(Qd, dev(w.pos_q, None), w.sections, w.base, out_scale=q_scale)
     kn = Kd[:, a:a + n_new]
     pk.pc_rope3d(kn, dev(w.pos_k[a:a + n_new], None), w.sections, w.base)
-    q_rot = orc.rope3d(w.Q, w.pos_q, w.sections, w.base)
+    q_rot = orc.rope3d(w.Q, w.pos_q, w.sections, w.base) * q_scale
     k_rot = orc.rope3d(w.K[:, a:a + n_new], w.pos_k[a:a + n_new], w.sections, w.base)
-    for got, want in ((host(Qd), q_rot), (host(kn), k_rot)):
-        assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-6)
+    for got, want, floor in ((host(Qd), q_rot, 1e-6 * min(q_scale, 1.0)), (host(kn), k_rot, 1e-6)):
+        assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + floor)
     assert torch.equal(Kd[:, :a], dev(w.K[:, :a], "bf16")), "rows outside the new frame must not change"
     del Qd, Kd, kn
 
@@ -69,8 +74,8 @@ def test_full_size_frame(frame):
 
     # ---- a2: importance of every key
     rows = dev(w.score_rows.astype(np.int32), None)
-    sc = pk.pc_score(Q, K, Nk, w.scale, q_rows=rows)
-    sco = orc.score(Qo[:, w.score_rows], Ko, w.scale)
+    sc = pk.pc_score(Q, K, Nk, scale, q_rows=rows)
+    sco = orc.score(Qo[:, w.score_rows], Ko, scale)
     got = host(sc).astype(np.float64)
     err = np.abs(got - sco)
     assert np.all(err <= 2e-7 + 2e-5 * sco), (err.max(), (err / (sco + 1e-30)).max())
@@ -111,15 +116,15 @@ def test_full_size_frame(frame):
     rs = synth.strided_rows(Nq, N_SAMPLE_ROWS)
     ig, nk = kept["idx"], kept["nk"]
     lse = torch.empty((Hq, Nq), dtype=torch.float32, device=DEV)
-    O = pk.pc_frame_attn(Q, kept["K"], kept["V"], nk, w.scale, lse=lse)
+    O = pk.pc_frame_attn(Q, kept["K"], kept["V"], nk, scale, lse=lse)
     Kk = np.stack([Ko[g][ig[g]] for g in range(Hkv)])
     Vk = np.stack([Vo[g][ig[g]] for g in range(Hkv)])
-    Ow, Lw = orc.frame_attn(Qo[:, rs], Kk, Vk, w.scale)
+    Ow, Lw = orc.frame_attn(Qo[:, rs], Kk, Vk, scale)
     err = np.abs(host(O)[:, rs].astype(np.float64) - Ow)
     assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
     assert np.abs(host(lse)[:, rs] - Lw).max() <= 1e-3
-    O = pk.pc_frame_attn(Q, K, V, Nk, w.scale, lse=lse)
-    Ow, Lw = orc.frame_attn(Qo[:, rs], Ko, Vo, w.scale)
+    O = pk.pc_frame_attn(Q, K, V, Nk, scale, lse=lse)
+    Ow, Lw = orc.frame_attn(Qo[:, rs], Ko, Vo, scale)
     err = np.abs(host(O)[:, rs].astype(np.float64) - Ow)
     assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
     assert np.abs(host(lse)[:, rs] - Lw).max() <= 1e-3
@@ -128,7 +133,7 @@ def test_full_size_frame(frame):
 def test_rolling_steps_at_full_frame_size():
     """The rolling step at the shape of the 28-layer rollout: 24 query / 8 KV heads, 48x84-token
     frames, 256 text tokens, 512 scoring rows, gamma 0.85 with a 512-token minimum, cache packed
-    in place, attention cut into key shares.  Every step starts from the ORACLE's cache after the
+    in place, attention cut into key shares, softmax scale folded into the queries.  Every step starts from the ORACLE's cache after the
     previous step (so a selection that falls inside the score band cannot carry over), and is
     compared with the oracle's next state: segment table, kept rows (bit-exact outside the band),
     moved K / V / positions, and the attention of 64 sampled query rows per head."""
@@ -138,14 +143,16 @@ def test_rolling_steps_at_full_frame_size():
     rnd = orc.round_to_bf16
     aK = rnd(orc.rope3d(case.anchor_K, case.anchor_pos, case.sections, case.base))
     frames = [(rnd(orc.rope3d(K, p, case.sections, case.base)), V, p) for K, V, p in case.frames]
-    queries = [rnd(orc.rope3d(Q, p, case.sections, case.base)) for Q, p in zip(case.queries, case.query_pos)]
+    q_scale, scale = pk.folded_q_scale(case.scale), pk.PC_SCALE_FOLDED   # the form bench.py's rollout runs
+    queries = [rnd(orc.rope3d(Q, p, case.sections, case.base) * q_scale)
+               for Q, p in zip(case.queries, case.query_pos)]
     n, Hkv = case.n_frame, case.Hkv
     rows = np.union1d(case.score_rows, synth.strided_rows(n, N_SAMPLE_ROWS))   # the rows the oracle is given
     score_sub = np.searchsorted(rows, case.score_rows)
     sample_sub = np.searchsorted(rows, synth.strided_rows(n, N_SAMPLE_ROWS))
     budget_fn = lambda w: orc.budget_pow(n, w, gamma, b_min)
     want = orc.rolling_rollout(aK, case.anchor_V, case.anchor_pos, case.anchor_segments, frames,
-                               [Q[:, rows] for Q in queries], case.scale, budget_fn, score_rows=score_sub)
+                               [Q[:, rows] for Q in queries], scale, budget_fn, score_rows=score_sub)
     capacity = case.anchor_K.shape[1] + n_steps * n
 
     def insert(layer, K, V, pos_h, kind, frame):
@@ -159,7 +166,8 @@ def test_rolling_steps_at_full_frame_size():
     exempted = 0
     for i, Q in enumerate(queries):
         layer = RollingLayer(case.Hq, Hkv, case.D, capacity, n, case.scale, mode="pow", gamma=gamma, b_min=b_min,
-                             n_score=case.score_rows.size, sections=case.sections, base=case.base, device=DEV)
+                             n_score=case.score_rows.size, sections=case.sections, base=case.base, device=DEV,
+                             fold_scale=True)
         assert np.array_equal(host(layer.q_rows), case.score_rows)
         if i == 0:
             pre = {"K": aK, "V": case.anchor_V, "segments": list(case.anchor_segments),
@@ -200,12 +208,12 @@ def test_rolling_steps_at_full_frame_size():
             for s in segs_pre:
                 budgets.append(per_d[d - 1] if s[2] == pk.PC_SEG_FRAME else s[1])
                 d -= s[2] == pk.PC_SEG_FRAME
-            sco = orc.score(Q[:, case.score_rows], K_pre, case.scale)
+            sco = orc.score(Q[:, case.score_rows], K_pre, scale)
             exempted += check_selection(idx, sco, segs_pre, budgets, band=BAND)
         Kg, Vg = host(layer.K[:, :nk]).astype(np.float64), host(layer.V[:, :nk]).astype(np.float64)
         for h in range(Hkv):
             assert np.array_equal(Kg[h], K_pre[h][idx[h]]) and np.array_equal(Vg[h], V_pre[h][idx[h]])
-        Ow, _ = orc.frame_attn(Q[:, rows[sample_sub]], Kg, Vg, case.scale)
+        Ow, _ = orc.frame_attn(Q[:, rows[sample_sub]], Kg, Vg, scale)
         err = np.abs(host(O)[:, rows[sample_sub]].astype(np.float64) - Ow)
         assert err.max() <= 2e-2 and err.mean() <= 2e-3, (i, err.max(), err.mean())
         if np.array_equal(pos_got, w["pos"]):
