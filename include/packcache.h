@@ -16,8 +16,9 @@
  *     The caller owns every buffer.  The library allocates no device memory: scratch is
  *     a caller-provided device workspace whose size the *_workspace_bytes calls return.
  *   - Device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
- *     default stream).  No call synchronises the stream; host outputs (segment tables,
- *     counts) never depend on device results.
+ *     default stream).  No call synchronises the stream (pc_compact_status, a check a
+ *     caller may ask for, is the one exception); host outputs (segment tables, counts)
+ *     never depend on device results.
  *   - Tensors are row-major with the head dimension D contiguous and rows dense
  *     (row stride = D elements); the stride between heads is passed in ELEMENTS.
  *   - dtype: PC_F32 is the correctness tier (D = 64 or 128), PC_BF16 the fast tier
