@@ -346,7 +346,7 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
   int32_t pval = 0;
   int64_t pdst = -1;
   static_assert(kRows * 3 <= kGatherThreads, "one thread per position component");
-  if ((share_heads ? h == 0 : true) && threadIdx.x < (r1 - r0) * 3) {
+  if ((share_heads ? h == 0 : true) && static_cast<int>(threadIdx.x) < (r1 - r0) * 3) {
     const int row = r0 + threadIdx.x / 3, comp = threadIdx.x % 3;
     const int src = min(max(idx_h[row], 0), Nk_in - 1);
     if (!kInPlace || src != row) {

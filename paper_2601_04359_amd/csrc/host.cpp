@@ -142,7 +142,7 @@ void dyadic(double gamma, uint64_t* mant, int* shift) {
 
 int active_window(int b_one, int w, int q_min) {
   if (q_min <= 0) return w;
-  return std::min<int64_t>(w, b_one / q_min);
+  return static_cast<int>(std::min<int64_t>(w, b_one / q_min));
 }
 
 // t_d = q_min + floor(free * num_d / den) with exact integers; leftovers to d = 1.

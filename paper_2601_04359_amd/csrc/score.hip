@@ -314,7 +314,7 @@ template <bool kUnitC>
 __global__ __launch_bounds__(kThreads, 1) void score_colpass_bf16(
     const uint16_t* __restrict__ Qs, const int32_t* __restrict__ q_rows, const uint16_t* __restrict__ K,
     const float* __restrict__ lse2, float* __restrict__ out, int64_t out_stride_h, int64_t out_stride_split,
-    int Hkv, int rep, int n_qs, int Nk, int64_t q_stride_h, int64_t k_stride_h, float c, int n_key_blocks,
+    int /*Hkv*/, int rep, int n_qs, int Nk, int64_t q_stride_h, int64_t k_stride_h, float c, int n_key_blocks,
     int n_qsplits) {
   extern __shared__ __align__(16) uint8_t smem_raw[];
   lds_u8* smem = (lds_u8*)smem_raw;
@@ -541,7 +541,7 @@ __global__ __launch_bounds__(64) void score_colpass_f32(const float* __restrict_
         const int qr = q_rows ? q_rows[r0 + e / D] : r0 + e / D;
         qs[e / D][e % D] = Qh[static_cast<int64_t>(qr) * D + e % D];
       }
-      if (threadIdx.x < nt) ls[threadIdx.x] = lse[static_cast<int64_t>(h) * n_qs + r0 + threadIdx.x];
+      if (static_cast<int>(threadIdx.x) < nt) ls[threadIdx.x] = lse[static_cast<int64_t>(h) * n_qs + r0 + threadIdx.x];
       __syncthreads();
       for (int j = 0; j < nt; ++j) {
         float dot = 0.f;
