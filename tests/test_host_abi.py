@@ -58,6 +58,25 @@ def test_budget_norm_and_half_match_oracle(L, rho, w, q_min):
     assert pk.pc_budget(pk.PC_BUDGET_SLIDE, 4084, w) == orc.budget_slide(4084, w)
 
 
+def test_budgets_match_oracle_on_random_parameters(L):
+    """Exact integer budgets for random decay factors (arbitrary doubles, not only short decimals),
+    frame sizes, window lengths and quotas: the library's big-integer arithmetic against the
+    oracle's rationals; and the invariants of Eq. 8 (fixed-budget rules add up to B_one)."""
+    rng = np.random.default_rng(2024)
+    for _ in range(400):
+        N, w = int(rng.integers(1, 9000)), int(rng.integers(0, 100))
+        gamma = float(rng.choice([rng.uniform(1e-3, 1.0), 1.0, 0.5, rng.uniform(0.9, 1.0)]))
+        q = int(rng.choice([0, rng.integers(0, 50), rng.integers(0, N + 1)]))
+        assert pk.pc_budget(pk.PC_BUDGET_POW, N, w, gamma, q) == orc.budget_pow(N, w, gamma, q), (N, w, gamma, q)
+        norm = pk.pc_budget(pk.PC_BUDGET_NORM, N, w, gamma, q)
+        half = pk.pc_budget(pk.PC_BUDGET_HALF, N, w, 0.0, q)
+        assert norm == orc.budget_norm(N, w, gamma, q), (N, w, gamma, q)
+        assert half == orc.budget_half(N, w, q), (N, w, q)
+        if w > 0:
+            assert sum(norm) == N and sum(half) == N
+            assert all(a >= b for a, b in zip(norm, norm[1:])) and all(a >= b for a, b in zip(half, half[1:]))
+
+
 def test_budget_half_series_from_the_paper(L):
     assert pk.pc_budget(pk.PC_BUDGET_HALF, 4096, 4) == [2048, 1024, 512, 512]
     assert pk.pc_budget(pk.PC_BUDGET_HALF, 4096, 1) == [4096]
