@@ -293,7 +293,7 @@ def compact(K, V, pos, sc, segments, budgets, share_heads: bool = False, valid=N
 # --------------------------------------------------------------------------------------
 def rolling_rollout(anchor_K, anchor_V, anchor_pos, anchor_segments, frames, queries, scale: float,
                     budget_fn, score_rows=None, share_heads: bool = False, rotate=None, query_pos=None,
-                    rebase_t_scale=None, storage=None):
+                    rebase_t_scale=None, storage=None, include_self: bool = False):
     """Generate-time cache management over several frame steps.
 
     anchor_K, anchor_V [Hkv][A][D], anchor_pos [A][3], anchor_segments: the always-kept
@@ -313,6 +313,11 @@ def rolling_rollout(anchor_K, anchor_V, anchor_pos, anchor_segments, frames, que
     step see one consistent set of coordinates.  The anchors keep theirs.
     storage: rounding applied to keys whenever they are written to the cache (the cache's
     storage format), and to rotated queries; None keeps fp64.
+    include_self: the frame being generated attends to its own keys too (attention inside a
+    frame is bidirectional, Eq. 2 / Sec. 3.1).  frames[i] is then appended when step i + 1
+    begins, as an always-kept SELF segment that takes part in the softmax of scoring and
+    attention but is never pruned; when the next step begins it turns into the newest past
+    frame (distance 1) and is pruned from then on.
     Each step: slide the window, append the newest frame, score all cached keys with the
     scoring rows of the step's queries, keep the per-frame top-budget keys (anchors whole),
     attend over what is left.  Returns one dict per step: K, V, pos, segments (the cache
@@ -341,8 +346,10 @@ def rolling_rollout(anchor_K, anchor_V, anchor_pos, anchor_segments, frames, que
                 K = np.concatenate([K[:, :a], store(Kr)], axis=1)
                 pos = np.concatenate([pos[:, :a], pr], axis=1)
                 shift += delta
-        if i >= 1:
-            Kf, Vf, pf = frames[i - 1]
+        if include_self:   # last step's own frame is a past frame from now on
+            segments = [(a, n, SEG_FRAME if kind == SEG_SELF else kind, f) for (a, n, kind, f) in segments]
+        if i >= 1 or include_self:
+            Kf, Vf, pf = frames[i if include_self else i - 1]
             pf = np.asarray(pf).copy()
             pf[:, 0] -= shift
             Kf = f64(Kf) if rotate is None else store(rope3d(Kf, pf, *rotate))
@@ -350,7 +357,7 @@ def rolling_rollout(anchor_K, anchor_V, anchor_pos, anchor_segments, frames, que
             K = np.concatenate([K, Kf], axis=1)
             V = np.concatenate([V, f64(Vf)], axis=1)
             pos = np.concatenate([pos, np.broadcast_to(pf[None], (hsel,) + pf.shape)], axis=1)
-            segments.append((at, Kf.shape[1], SEG_FRAME, i))
+            segments.append((at, Kf.shape[1], SEG_SELF if include_self else SEG_FRAME, i + 1 if include_self else i))
         if rotate is None:
             Q = f64(Q)
         else:

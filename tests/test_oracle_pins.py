@@ -469,6 +469,52 @@ def test_rolling_rollout_survivors_are_nested_and_counts_follow_the_budgets():
     assert np.array_equal(steps[1]["K"], Kp) and np.array_equal(steps[1]["pos"], pp)
 
 
+def test_rolling_rollout_with_self_keys_and_full_budgets_is_attention_over_everything_so_far():
+    # the frame being generated sees its own keys too (Eq. 2: bidirectional inside a frame):
+    # with nothing pruned, step i is plain attention over anchors + frames 1..i
+    aK, aV, apos, asegs, frames, queries = _tiny_rolling()
+    steps = orc.rolling_rollout(aK, aV, apos, asegs, frames, queries, 0.3, lambda w: [5] * w, include_self=True)
+    for i, st in enumerate(steps):
+        K = np.concatenate([aK] + [f[0] for f in frames[:i + 1]], axis=1)
+        V = np.concatenate([aV] + [f[1] for f in frames[:i + 1]], axis=1)
+        O, L = orc.frame_attn(queries[i], K, V, 0.3)
+        np.testing.assert_allclose(st["O"], O, rtol=0, atol=1e-13)
+        np.testing.assert_allclose(st["lse"], L, rtol=0, atol=1e-13)
+        kinds = [s[2] for s in st["segments"]]
+        assert kinds == [orc.SEG_TEXT] + [orc.SEG_FRAME] * i + [orc.SEG_SELF]
+
+
+def test_rolling_rollout_with_self_keys_matches_step_by_step_brute_force():
+    # as the brute-force restatement above, with the step's own frame in the cache: it takes part
+    # in the softmax that scores the others, is never pruned at its own step, and is pruned as the
+    # newest past frame from the next step on
+    aK, aV, apos, asegs, frames, queries = _tiny_rolling(seed=13)
+    budget = lambda w: orc.budget_pow(5, w, 0.6, 1)          # 3, 1, 1, ...
+    steps = orc.rolling_rollout(aK, aV, apos, asegs, frames, queries, 0.3, budget, include_self=True)
+    cache = [("a", i) for i in range(3)]
+    rowK = {("a", i): aK[0, i] for i in range(3)}
+    for step, Q in enumerate(queries):
+        own = step + 1                                         # id of the frame being generated
+        for t in range(5):
+            cache.append((own, t))
+            rowK[(own, t)] = frames[step][0][0, t]
+        Kc = np.stack([rowK[c] for c in cache])[None]
+        sc = orc.score_bruteforce(Q, Kc, 0.3)[0]
+        b = budget(step)
+        keep = [c for c in cache if c[0] == "a"]
+        for j in range(1, step + 1):                           # past frames: distance own - j
+            rows = [(sc[r], r) for r, c in enumerate(cache) if c[0] == j]
+            rows.sort(key=lambda x: (-x[0], x[1]))
+            keep += [cache[r] for r in sorted(r for _, r in rows[:b[own - j - 1]])]
+        keep += [c for c in cache if c[0] == own]              # the step's own frame stays whole
+        cache = keep
+        got = [("a", int(p[1])) if p[0] < 10 else (int(p[0]) - 10, int(p[1])) for p in steps[step]["pos"][0]]
+        assert got == cache, f"step {step + 1}"
+        # and the output is plain attention over exactly these rows
+        Kk = np.stack([rowK[c] for c in cache])[None]
+        assert np.array_equal(steps[step]["K"], Kk)
+
+
 def test_rolling_rollout_sliding_window_keeps_only_the_newest_frame():
     aK, aV, apos, asegs, frames, queries = _tiny_rolling(seed=1)
     steps = orc.rolling_rollout(aK, aV, apos, asegs, frames, queries, 0.3, lambda w: orc.budget_slide(5, w))
