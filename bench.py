@@ -56,6 +56,9 @@ def main() -> int:
     ap.add_argument("--rollout-passes", type=int, default=1,
                     help="attention passes per frame and layer (iterative decoding): with more than one, the "
                          "first pass runs on the un-packed cache and its log-sum-exp feeds the scoring")
+    ap.add_argument("--rollout-self", action="store_true",
+                    help="the frame being generated also sits in the cache (always-kept SELF segment of its own "
+                         "step, the newest past frame from the next step on): Eq. 2's attention inside the frame")
     ap.add_argument("--out-dir", default=os.path.join(ROOT, "gpurun_out"), help="where the per-frame tables go")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-f48", action="store_true", help="skip the frame-48 compaction / dense legs")
@@ -354,9 +357,10 @@ def main() -> int:
         n_anchor = n_text + n
         sections, scale5 = (32, 48, 48), 1.0 / float(np.sqrt(D))
         tok_budget = n            # NORM / HALF / SLIDE: one frame's worth of tokens over all past frames
+        own = args.rollout_self
         cap_packed = n_anchor + n + (sum(pk.pc_budget(pk.PC_BUDGET_POW, n, F - 1, 0.85, 512))
-                                     if args.rollout_mode == "pow" else tok_budget + n)
-        cap_dense = n_anchor + (F - 1) * n
+                                     if args.rollout_mode == "pow" else tok_budget + n) + (n if own else 0)
+        cap_dense = n_anchor + (F - 1) * n + (n if own else 0)
         streams = [synth.DeviceRollingStream(1000 * (l + 1), hq5, hkv5, D, F, sections, dev) for l in range(L)]
         packed = [RollingLayer(hq5, hkv5, D, cap_packed, n, scale5, mode=args.rollout_mode, gamma=0.85, b_min=512,
                                budget_tokens=tok_budget, n_score=512, sections=sections, device=dev, fold_scale=fold)
@@ -384,13 +388,19 @@ def main() -> int:
         for f in range(1, F + 1):
             fpos = up(synth.grid_positions(f, gh, gw, n_text), bf=False)
             ppos = up(synth.grid_positions(f - 1, gh, gw, n_text), bf=False) if f >= 2 else None
+            # the frame appended at this step: the one generated last, or (--rollout-self) this step's own
+            new_f, new_pos = (f, fpos) if own else (f - 1, ppos)
+            new_kind = pk.PC_SEG_SELF if own else pk.PC_SEG_FRAME
             for l in range(L):           # untimed: draw this step's inputs into the caches / query buffers
                 streams[l].queries(f, Qp[l])
                 Qd[l].copy_(Qp[l])
-                if f >= 2:
+                if own:
+                    packed[l].promote_self()
+                    dense[l].promote_self()
+                if new_f >= 1:
                     k, v, p = packed[l].reserve(n)
-                    streams[l].frame(f - 1, k, v)
-                    p.copy_(ppos[None].expand(hkv5, n, 3))
+                    streams[l].frame(new_f, k, v)
+                    p.copy_(new_pos[None].expand(hkv5, n, 3))
                     kd, vd, pd = dense[l].reserve(n)
                     kd.copy_(k); vd.copy_(v); pd.copy_(p)
             torch.cuda.synchronize()
@@ -399,8 +409,8 @@ def main() -> int:
                 a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 a.record()
                 for l in range(L):
-                    if f >= 2:
-                        layers[l].commit(n, pk.PC_SEG_FRAME, f - 1, rotate_with=ppos)
+                    if new_f >= 1:
+                        layers[l].commit(n, new_kind, new_f, rotate_with=new_pos)
                     if args.rollout_passes == 1:
                         layers[l].step(Qs[l], O=O5, q_pos=fpos)
                     else:
@@ -417,7 +427,7 @@ def main() -> int:
         tp, td = sum(r["packed_ms"] for r in curve), sum(r["dense_ms"] for r in curve)
         last4 = curve[-4:]
         out["rollout"] = {"layers": L, "frames": F, "Hq": hq5, "Hkv": hkv5, "mode": args.rollout_mode,
-                          "passes_per_frame": args.rollout_passes,
+                          "passes_per_frame": args.rollout_passes, "own_frame_in_cache": own,
                           "packed_total_s": round(tp / 1e3, 4), "dense_total_s": round(td / 1e3, 4),
                           "speedup_total": round(td / tp, 3),
                           "speedup_last4": round(sum(r["dense_ms"] for r in last4) / sum(r["packed_ms"] for r in last4), 3),

@@ -9,6 +9,11 @@ step of the path runs in libpackcache kernels.  Per frame step (Sec. 3.4, Fig. 5
     pc_compact          in place: anchors stay, each past frame keeps its top-budget keys
     pc_frame_attn       the step's queries over the packed cache
 
+The frame being generated may sit in the cache too (attention inside a frame is
+bidirectional, Eq. 2): commit it with kind PC_SEG_SELF before step(); it takes part in the
+softmax of scoring and attention, is never pruned at its own step, and promote_self() turns
+it into the newest past frame when the next step begins, without moving a row.
+
 A model that makes several attention passes per frame (iterative decoding) calls attend()
 on the un-packed cache first, hands its log-sum-exp to refresh() and makes the remaining
 passes on the packed cache: the compaction is paid once per frame.
@@ -91,6 +96,13 @@ class RollingLayer:
             pk.pc_rope3d(self.K[:, a:a + n], rotate_with, self.sections, self.base)
         self.segments.append((a, n, kind, frame))
         self.nk = a + n
+
+    def promote_self(self) -> None:
+        """Call when a step begins: the frame that was generated last and sat in the cache as the
+        always-kept SELF segment of its own step (commit(..., kind=PC_SEG_SELF)) becomes the newest
+        past frame.  A table edit only: its rows are already in place."""
+        self.segments = [(a, n, pk.PC_SEG_FRAME if kind == pk.PC_SEG_SELF else kind, f)
+                         for (a, n, kind, f) in self.segments]
 
     def advance_window(self) -> int:
         """Call when a step begins, before reserve(): drops the oldest frame segments that

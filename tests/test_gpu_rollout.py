@@ -82,6 +82,39 @@ def test_rolling_layer_matches_oracle(mode, gamma, b_min, share, fold):
         assert [s[1] for s in layer.segments if s[2] == pk.PC_SEG_FRAME] == [0] * (len(frames) - 2) + [n]
 
 
+@pytest.mark.parametrize("mode,gamma,b_min,share,fold", [("pow", 0.85, 32, False, False), ("half", 1.0, 40, True, True)])
+def test_rolling_layer_with_the_steps_own_frame_in_the_cache(mode, gamma, b_min, share, fold):
+    """The frame being generated is in the cache as an always-kept SELF segment (Eq. 2: attention
+    inside a frame is bidirectional) and becomes the newest past frame at the next step by a
+    table edit; against the oracle's rollout with include_self."""
+    case = synth.rolling_case(seed=17, n_steps=5)
+    aK, frames, queries = _rotated(case, pk.folded_q_scale(case.scale) if fold else 1.0)
+    want = orc.rolling_rollout(aK, case.anchor_V, case.anchor_pos, case.anchor_segments, frames, queries,
+                               pk.PC_SCALE_FOLDED if fold else case.scale, _budget_fn(mode, case, gamma, b_min),
+                               score_rows=case.score_rows, share_heads=share, include_self=True)
+    n = case.n_frame
+    layer = RollingLayer(case.Hq, case.Hkv, case.D, case.anchor_K.shape[1] + (len(frames) + 1) * n, n, case.scale,
+                         mode=mode, gamma=gamma, b_min=b_min, n_score=case.score_rows.size,
+                         sections=case.sections, base=case.base, device=DEV, share_heads=share, fold_scale=fold)
+    for (start, length, kind, frame) in case.anchor_segments:
+        _insert(layer, aK[:, start:start + length], case.anchor_V[:, start:start + length],
+                case.anchor_pos[start:start + length], kind, frame)
+    for i, Q in enumerate(queries):
+        layer.promote_self()
+        Kf, Vf, pf = frames[i]
+        _insert(layer, Kf, Vf, pf, pk.PC_SEG_SELF, i + 1)
+        O = layer.step(dev(Q.astype(np.float32), "bf16"))
+        w = want[i]
+        assert layer.segments == w["segments"], (mode, i)
+        nk = layer.nk
+        assert nk == w["K"].shape[1] and layer.segments[-1] == (nk - n, n, pk.PC_SEG_SELF, i + 1)
+        assert np.array_equal(host(layer.pos[:, :nk]), w["pos"]), f"step {i + 1}: kept set differs"
+        assert np.array_equal(host(layer.K[:, :nk]).astype(np.float64), w["K"])
+        assert np.array_equal(host(layer.V[:, :nk]).astype(np.float64), w["V"])
+        err = np.abs(host(O).astype(np.float64) - w["O"])
+        assert err.max() <= 2e-2 and err.mean() <= 2e-3, (mode, i, err.max(), err.mean())
+
+
 def test_rotation_on_insert_equals_standalone_rotation():
     case = synth.rolling_case(seed=3, n_steps=2)
     n = case.n_frame
