@@ -56,6 +56,10 @@ def main() -> int:
     ap.add_argument("--rollout-passes", type=int, default=1,
                     help="attention passes per frame and layer (iterative decoding): with more than one, the "
                          "first pass runs on the un-packed cache and its log-sum-exp feeds the scoring")
+    ap.add_argument("--rollout-window", type=int, default=0,
+                    help="with --rollout-mode half | norm: a sliding window of this many past frames (minimum "
+                         "quota B_one // W, so that older frames get nothing and leave: FIFO truncation), the "
+                         "retained rows rebased in time whenever the window advances")
     ap.add_argument("--rollout-self", action="store_true",
                     help="the frame being generated also sits in the cache (always-kept SELF segment of its own "
                          "step, the newest past frame from the next step on): Eq. 2's attention inside the frame")
@@ -362,7 +366,11 @@ def main() -> int:
                                      if args.rollout_mode == "pow" else tok_budget + n) + (n if own else 0)
         cap_dense = n_anchor + (F - 1) * n + (n if own else 0)
         streams = [synth.DeviceRollingStream(1000 * (l + 1), hq5, hkv5, D, F, sections, dev) for l in range(L)]
-        packed = [RollingLayer(hq5, hkv5, D, cap_packed, n, scale5, mode=args.rollout_mode, gamma=0.85, b_min=512,
+        window = args.rollout_window
+        if window and args.rollout_mode not in ("half", "norm"):
+            raise SystemExit("--rollout-window needs --rollout-mode half or norm")
+        packed = [RollingLayer(hq5, hkv5, D, cap_packed, n, scale5, mode=args.rollout_mode, gamma=0.85,
+                               b_min=tok_budget // window if window else 512, slide_t_scale=4 if window else None,
                                budget_tokens=tok_budget, n_score=512, sections=sections, device=dev, fold_scale=fold)
                   for _ in range(L)]
         dense = [RollingLayer(hq5, hkv5, D, cap_dense, n, scale5, mode="dense", sections=sections, device=dev,
@@ -385,11 +393,33 @@ def main() -> int:
         O5 = torch.empty_like(Qp[0])
         lse5 = torch.empty((hq5, n), dtype=torch.float32, device=dev)
         curve = []
+        rebase_ms_total = 0.0
         for f in range(1, F + 1):
-            fpos = up(synth.grid_positions(f, gh, gw, n_text), bf=False)
+            rebase_ms = 0.0
+            if window:        # the window advances when the step begins; the rebase is part of the packed step
+                a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for l in range(L):
+                    packed[l].advance_window()
+                e.record()
+                torch.cuda.synchronize()
+                rebase_ms = a.elapsed_time(e)
+                rebase_ms_total += rebase_ms
+            shift = packed[0].shift   # everything that arrives from now on is placed at its time minus the shift
+            fpos_h = synth.grid_positions(f, gh, gw, n_text)
+            fpos = up(fpos_h, bf=False)
             ppos = up(synth.grid_positions(f - 1, gh, gw, n_text), bf=False) if f >= 2 else None
+            if shift:
+                fpos_h = fpos_h.copy()
+                fpos_h[:, 0] -= shift
+                fpos_shifted = up(fpos_h, bf=False)
+                ppos_shifted = ppos.clone()
+                ppos_shifted[:, 0] -= shift
+            else:
+                fpos_shifted, ppos_shifted = fpos, ppos
             # the frame appended at this step: the one generated last, or (--rollout-self) this step's own
             new_f, new_pos = (f, fpos) if own else (f - 1, ppos)
+            new_pos_packed = fpos_shifted if own else ppos_shifted
             new_kind = pk.PC_SEG_SELF if own else pk.PC_SEG_FRAME
             for l in range(L):           # untimed: draw this step's inputs into the caches / query buffers
                 streams[l].queries(f, Qp[l])
@@ -400,21 +430,22 @@ def main() -> int:
                 if new_f >= 1:
                     k, v, p = packed[l].reserve(n)
                     streams[l].frame(new_f, k, v)
-                    p.copy_(new_pos[None].expand(hkv5, n, 3))
+                    p.copy_(new_pos_packed[None].expand(hkv5, n, 3))
                     kd, vd, pd = dense[l].reserve(n)
-                    kd.copy_(k); vd.copy_(v); pd.copy_(p)
+                    kd.copy_(k); vd.copy_(v); pd.copy_(new_pos[None].expand(hkv5, n, 3))
             torch.cuda.synchronize()
             times = {}
             for name, layers, Qs in (("packed", packed, Qp), ("dense", dense, Qd)):
                 a, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 a.record()
+                rot_new, rot_q = (new_pos_packed, fpos_shifted) if name == "packed" else (new_pos, fpos)
                 for l in range(L):
                     if new_f >= 1:
-                        layers[l].commit(n, new_kind, new_f, rotate_with=new_pos)
+                        layers[l].commit(n, new_kind, new_f, rotate_with=rot_new)
                     if args.rollout_passes == 1:
-                        layers[l].step(Qs[l], O=O5, q_pos=fpos)
+                        layers[l].step(Qs[l], O=O5, q_pos=rot_q)
                     else:
-                        pk.pc_rope3d(Qs[l], fpos, sections, 10000.0, out_scale=layers[l].q_out_scale)
+                        pk.pc_rope3d(Qs[l], rot_q, sections, 10000.0, out_scale=layers[l].q_out_scale)
                         layers[l].attend(Qs[l], O=O5, lse=lse5)
                         layers[l].refresh(Qs[l], lse=lse5)
                         for _ in range(args.rollout_passes - 1):
@@ -422,12 +453,15 @@ def main() -> int:
                 e.record()
                 torch.cuda.synchronize()
                 times[name] = a.elapsed_time(e)
+            times["packed"] += rebase_ms
             curve.append({"frame": f, "Nk_dense": dense[0].nk, "Nk_packed": packed[0].nk,
                           "dense_ms": round(times["dense"], 3), "packed_ms": round(times["packed"], 3)})
         tp, td = sum(r["packed_ms"] for r in curve), sum(r["dense_ms"] for r in curve)
         last4 = curve[-4:]
         out["rollout"] = {"layers": L, "frames": F, "Hq": hq5, "Hkv": hkv5, "mode": args.rollout_mode,
                           "passes_per_frame": args.rollout_passes, "own_frame_in_cache": own,
+                          "window_frames": window or None, "rebase_total_ms": round(rebase_ms_total, 3) if window else None,
+                          "time_shift_at_end": packed[0].shift,
                           "packed_total_s": round(tp / 1e3, 4), "dense_total_s": round(td / 1e3, 4),
                           "speedup_total": round(td / tp, 3),
                           "speedup_last4": round(sum(r["dense_ms"] for r in last4) / sum(r["packed_ms"] for r in last4), 3),
