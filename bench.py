@@ -300,6 +300,27 @@ def main() -> int:
         Kw, Vw, pw = layers[0][0], layers[0][1], layers[0][2]
         dense48_ms = timed(lambda: pk.pc_frame_attn(Q48, K48, V48, Nk48, call_scale, O=O48), 2)
         score48_ms = timed(lambda: pk.pc_score(Q48, K48, Nk48, call_scale, score=sc48, ws=ws_s48, q_rows=rows48), 3)
+        # Cache mask in front of the select (Sec. 3.1 / 3.4): a seeded frame-level Bernoulli(1/2) mask over
+        # the past frames' tokens; masked tokens are never candidates and are physically removed.
+        mrng = np.random.default_rng(48)
+        valid_h = np.ones(Nk48, dtype=np.uint8)
+        for (a0, ln, kind, _) in w48.segments:
+            if kind == pk.PC_SEG_FRAME:
+                valid_h[a0:a0 + ln] = mrng.random(ln) < 0.5
+        valid_d = torch.from_numpy(valid_h).to(dev)
+        b48 = pk.segment_budgets(w48.segments, pk.pc_budget(pk.PC_BUDGET_POW, w48.n_frame, 47, 0.85, 512))
+        t0 = time.perf_counter()
+        b48m = pk.pc_masked_budgets(w48.segments, b48, valid_h)
+        masked_budget_host_ms = (time.perf_counter() - t0) * 1e3
+        sc48m = sc48.clone()
+        mask_ms = timed(lambda: pk.pc_mask_scores(sc48m, valid_d), 5)
+        KL[0].copy_(K48), VL[0].copy_(V48), PL[0].copy_(pos48)
+        masked_compact_ms = timed(lambda: pk.pc_compact(KL[0], VL[0], PL[0], sc48m, w48.segments, b48m, ws=ws_c48), 1)
+        out["cache_mask_f48"] = {"masked_tokens": int((valid_h == 0).sum()), "kept_rows": int(sum(b48m)),
+                                 "kept_rows_without_mask": int(sum(b48)),
+                                 "pc_masked_budgets_host_ms": round(masked_budget_host_ms, 3),
+                                 "pc_mask_scores_ms": round(mask_ms, 4),
+                                 "pc_compact_in_place_ms": round(masked_compact_ms, 4)}
         out["compaction_f48_in_place"] = comp
         out["compaction_f48_in_place_batched"] = comp_b
         out["compaction_f48_in_place_two_streams"] = comp_p
