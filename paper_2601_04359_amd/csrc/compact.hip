@@ -7,7 +7,7 @@
 //            are taken lowest index first; the kept indices come out ascending.  Segments
 //            longer than PC_MAX_SELECT_LEN take a one-wave, bit-by-bit variant that re-reads
 //            the scores.
-//   gather   HBM-bound.  A work-group owns 32 (in place: 64) consecutive packed rows of one
+//   gather   HBM-bound.  A work-group owns 64 consecutive packed rows of one
 //            KV head: it loads its K, V and position rows (16 bytes per lane), then stores
 //            them.  In place, a work-group may only store once every work-group whose SOURCE
 //            rows lie in its destination range has finished loading.  Work-groups take their
@@ -25,8 +25,12 @@
 namespace pc {
 namespace {
 
-constexpr int kGatherRows = 32;   // packed rows per gather work-group
-constexpr int kGatherThreads = 256;
+// Packed rows per gather work-group and its size: a thread moves two 16-byte pieces of K and two
+// of V.  Measured on 28 layer caches at frame 48 (gamma 0.85): 4 pieces per thread (64 rows, 256
+// threads) 931 us, 2 pieces (32 rows, 256 threads) 838 us, (64 rows, 512 threads) 812 us, 1 piece
+// (32 rows, 512 threads) 931 us.
+constexpr int kGatherRows = 64;
+constexpr int kGatherThreads = 512;
 constexpr int kSpinLimit = 1 << 22;
 
 struct SegTable {
@@ -612,9 +616,7 @@ extern "C" int pc_compact_batch_phase(int phases, int n_layers, void* K, void* V
   if (!(phases & PC_COMPACT_GATHER)) return PC_OK;
 
   const int cpr = row_bytes / 16;
-  constexpr int kRowsInPlace = 64;
-  const int rows_per_group = in_place ? kRowsInPlace : kGatherRows;
-  const int chunks_per_head = ceil_div(nk_out, rows_per_group);
+  const int chunks_per_head = ceil_div(nk_out, kGatherRows);
   const int64_t in_stride_c = kv_stride_h * elt / 16, out_stride_c = kv_out_stride_h * elt / 16;
   const dim3 ggrid(chunks_per_head * Hkv * n_layers);
   PC_REQUIRE(!in_place || Hkv * n_layers <= kMaxTicketHeads, PC_ERR_UNSUPPORTED,
@@ -627,9 +629,9 @@ extern "C" int pc_compact_batch_phase(int phases, int n_layers, void* K, void* V
       out_stride_c, pos_stride_h, pos_out_stride_h, sync, flags, lay.chunks_per_head, tab, n_layers,      \
       in_stride_lc, out_stride_lc, pos_stride_l, pos_out_stride_l, idx_stride_layer)
   if (cpr == 16) {
-    if (in_place) PC_LAUNCH_GATHER(16, kRowsInPlace, true); else PC_LAUNCH_GATHER(16, kGatherRows, false);
+    if (in_place) PC_LAUNCH_GATHER(16, kGatherRows, true); else PC_LAUNCH_GATHER(16, kGatherRows, false);
   } else if (cpr == 32) {
-    if (in_place) PC_LAUNCH_GATHER(32, kRowsInPlace, true); else PC_LAUNCH_GATHER(32, kGatherRows, false);
+    if (in_place) PC_LAUNCH_GATHER(32, kGatherRows, true); else PC_LAUNCH_GATHER(32, kGatherRows, false);
   } else {
     PC_FAIL(PC_ERR_UNSUPPORTED, "pc_compact: rows of %d bytes (supported: 256 and 512)", row_bytes);
   }
