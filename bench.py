@@ -25,9 +25,9 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # this script whose summaries are committed under profiles/ (FETCH_SIZE counter x 1.9998 + WRITE_SIZE
 # x 1.0000, the factors a plain 256 MiB device copy in the same runs gave).  They hold for the
 # default workload only and are reported, not re-measured, here.
-TRAFFIC_ATTN_F24_PACKED_BYTES = int((67265.4 * 1.9998 + 16128.0) * 1024)
-TRAFFIC_COMPACT_F48_G085_BYTES = int((41619.9 * 1.9998 + 76947.1) * 1024)   # per layer, in place
-TRAFFIC_COMPACT_BATCH_F48_G085_BYTES = int((1163304.8 * 1.9998 + 2154487.6) * 1024 / 28)   # per layer, one call
+TRAFFIC_ATTN_F24_PACKED_BYTES = int((67264.8 * 1.9998 + 16128.0) * 1024)
+TRAFFIC_COMPACT_F48_G085_BYTES = int((41606.4 * 1.9998 + 76952.8) * 1024)   # per layer, in place
+TRAFFIC_COMPACT_BATCH_F48_G085_BYTES = int((1163569.6 * 1.9998 + 2154639.1) * 1024 / 28)   # per layer, one call
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
