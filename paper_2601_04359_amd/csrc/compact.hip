@@ -132,17 +132,22 @@ __global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ sc
   select_wave<kItems>(score + sc_off + start, len, keep, out, start);
 }
 
-// Four waves per segment: wave w owns the contiguous slice [w * 64 kItems, (w+1) * 64 kItems)
-// of the segment, kItems keys per lane in registers.  The k-th largest key is found eight
-// bits at a time: keys that still match the prefix vote into a 256-bin LDS histogram, the
-// 256 threads take a suffix sum over the bins (wave scan + one exchange) and the bin that
-// contains the k-th key extends the prefix; as soon as that bin holds a single key, the
-// key itself is the threshold and the remaining passes are skipped.  The histogram is kept in
-// four copies laid out [bin][lane % 4], which spreads the votes of one instruction for a crowded
-// bin over four addresses; more copies cost more to clear and to add up than the shorter
-// queues save once a stack of layers fills the chip with these work-groups (the kernel is then
-// bound by its instruction count).  The ordered output needs one more exchange (keys above the
-// threshold and keys equal to it, per wave).
+// One work-group of 256 threads per segment; thread t keeps the kItems CONSECUTIVE keys
+// [t kItems, (t+1) kItems) of the segment in registers as order-preserving integers.
+//   * The bits all keys share (sign, most of the exponent) are found with one AND / OR reduction
+//     and skipped.
+//   * The k-th largest key is then found eleven bits at a time: keys that still match the prefix
+//     vote into a 2,048-bin LDS histogram; a thread owns eight neighbouring bins, the 256 threads
+//     take a suffix sum over their totals (wave scan + one exchange) and the thread whose bins
+//     contain the k-th key walks its eight.  With 4,032 keys over 2,048 bins the chosen bin
+//     nearly always holds a single key, which then IS the threshold and ends the search; two
+//     passes are the usual worst case.
+//   * Output in ascending index order: with consecutive keys per thread a kept key's position is
+//     (kept keys of lower threads) + (kept keys earlier in this thread), so one more scan over
+//     the threads (keys above the threshold and keys equal to it, packed in one word) places
+//     everything; equal keys are taken lowest index first.
+// The kernel is bound by its instruction count once a stack of layers fills the chip with these
+// work-groups, hence few, wide passes and no per-key cross-lane work.
 // Blocks also clear the in-place gather's ticket counters and flags (n_clear words).
 template <int kItems>
 __global__ __launch_bounds__(256) void select_block_kernel(const float* __restrict__ score,
@@ -151,11 +156,12 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
                                                            SegTable tab, int32_t* __restrict__ clear,
                                                            int n_clear, int hsel, int64_t score_stride_l,
                                                            int64_t idx_stride_l) {
-  constexpr int kCopies = 4;
-  __shared__ __align__(16) int s_hist[256 * kCopies];
+  constexpr int kBits = 11, kBins = 1 << kBits, kOwn = kBins / 256;  // bins per thread
+  static_assert(kOwn == 8, "a thread reads its bins with two 16-byte loads");
+  __shared__ __align__(16) int s_hist[kBins];
   __shared__ int s_wave_sum[4];
   __shared__ int s_pick[4];  // chosen digit, keys above it, keys in it, the key when it is alone
-  __shared__ int s_gt[4], s_eq[4];
+  __shared__ uint32_t s_and[4], s_or[4];
   const int s = blockIdx.x, h = blockIdx.y;
   {
     const int nb = gridDim.x * gridDim.y, b = h * gridDim.x + s;
@@ -169,22 +175,37 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
     return;
   }
   const float* sc = score + (h / hsel) * score_stride_l + (h % hsel) * score_stride_h + start;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const uint64_t lt_mask = (1ull << lane) - 1ull;
-  const int base = wave * 64 * kItems;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int e0 = t * kItems;
   uint32_t key[kItems];
+  if constexpr (kItems % 4 == 0) {
+    const bool aligned = (reinterpret_cast<uintptr_t>(sc) & 15) == 0;  // block-uniform
 #pragma unroll
-  for (int i = 0; i < kItems; ++i) {
-    const int e = base + i * 64 + lane;
-    key[i] = e < len ? order_key(sc[e]) : 0u;  // 0 is below every real key
+    for (int q = 0; q < kItems / 4; ++q) {
+      const int e = e0 + q * 4;
+      float v[4] = {0.f, 0.f, 0.f, 0.f};
+      if (aligned && e + 3 < len) {
+        const f32x4 x = *reinterpret_cast<const f32x4*>(sc + e);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = x[j];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (e + j < len) v[j] = sc[e + j];
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) key[q * 4 + j] = e + j < len ? order_key(v[j]) : 0u;  // 0 is below every real key
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kItems; ++i) key[i] = e0 + i < len ? order_key(sc[e0 + i]) : 0u;
   }
-  // Bits shared by every key of the segment (sign, most of the exponent) are settled at
-  // once: only the bits from the highest differing one down go through the histogram,
-  // which also keeps the votes from piling onto a single bin.
+  // Bits shared by every key of the segment are settled at once: only the bits from the highest
+  // differing one down go through the histogram.
   uint32_t k_and = 0xFFFFFFFFu, k_or = 0u;
 #pragma unroll
   for (int i = 0; i < kItems; ++i) {
-    if (base + i * 64 + lane < len) {
+    if (e0 + i < len) {
       k_and &= key[i];
       k_or |= key[i];
     }
@@ -195,35 +216,36 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
     k_or |= __shfl_xor(k_or, d, 64);
   }
   if (lane == 0) {
-    s_gt[wave] = static_cast<int>(k_and);
-    s_eq[wave] = static_cast<int>(k_or);
+    s_and[wave] = k_and;
+    s_or[wave] = k_or;
   }
   __syncthreads();
-  k_and = static_cast<uint32_t>(s_gt[0] & s_gt[1] & s_gt[2] & s_gt[3]);
-  k_or = static_cast<uint32_t>(s_eq[0] | s_eq[1] | s_eq[2] | s_eq[3]);
-  __syncthreads();
+  k_and = s_and[0] & s_and[1] & s_and[2] & s_and[3];
+  k_or = s_or[0] | s_or[1] | s_or[2] | s_or[3];
   const uint32_t differ = k_and ^ k_or;
   int hi = differ ? 32 - __clz(differ) : 0;  // number of undecided low bits
   uint32_t prefix = hi >= 32 ? 0u : (k_or >> hi) << hi;
   int remaining = k;
+  int4* h4 = reinterpret_cast<int4*>(s_hist);
   while (hi > 0) {
-    const int width = min(8, hi), shift = hi - width;
-    reinterpret_cast<int4*>(s_hist)[threadIdx.x] = make_int4(0, 0, 0, 0);  // bin threadIdx.x, all copies
+    const int width = min(kBits, hi), shift = hi - width;
+    h4[2 * t] = make_int4(0, 0, 0, 0);  // this thread's own eight bins
+    h4[2 * t + 1] = make_int4(0, 0, 0, 0);
     __syncthreads();
     const uint32_t hi_mask = hi >= 32 ? 0u : 0xFFFFFFFFu << hi;
     const uint32_t digit_mask = (1u << width) - 1u;
 #pragma unroll
-    for (int i = 0; i < kItems; ++i) {
-      const int e = base + i * 64 + lane;
-      if (e < len && (key[i] & hi_mask) == (prefix & hi_mask))
-        atomicAdd(&s_hist[((key[i] >> shift) & digit_mask) * kCopies + (lane & (kCopies - 1))], 1);
-    }
+    for (int i = 0; i < kItems; ++i)
+      if (e0 + i < len && (key[i] & hi_mask) == (prefix & hi_mask))
+        atomicAdd(&s_hist[(key[i] >> shift) & digit_mask], 1);
     __syncthreads();
-    static_assert(kCopies == 4, "a thread adds up its bin's copies with one 16-byte read");
-    const int4 votes = reinterpret_cast<const int4*>(s_hist)[threadIdx.x];
-    const int mine = votes.x + votes.y + votes.z + votes.w;  // votes for bin threadIdx.x
-    // suffix sums: above = number of matching keys with a digit larger than this thread's
-    int incl = mine;  // inclusive suffix sum inside the wave (towards higher lanes)
+    const int4 lo4 = h4[2 * t], hi4 = h4[2 * t + 1];
+    const int c[kOwn] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+    int mine = 0;  // votes for bins 8 t .. 8 t + 7
+#pragma unroll
+    for (int j = 0; j < kOwn; ++j) mine += c[j];
+    // suffix sums over the threads: above = matching keys with a digit beyond this thread's bins
+    int incl = mine;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
       const int v = __shfl_down(incl, d, 64);
@@ -233,10 +255,21 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
     __syncthreads();
     int above = incl - mine;
     for (int w = wave + 1; w < 4; ++w) above += s_wave_sum[w];
-    if (above < remaining && remaining <= above + mine) {  // exactly one thread
-      s_pick[0] = threadIdx.x;
-      s_pick[1] = above;
-      s_pick[2] = mine;
+    if (above < remaining && remaining <= above + mine) {  // exactly one thread: walk its bins downwards
+      int ab = above, digit = 0, cnt = 0;
+      bool found = false;
+#pragma unroll
+      for (int j = kOwn - 1; j >= 0; --j) {
+        if (!found && remaining <= ab + c[j]) {
+          found = true;
+          digit = t * kOwn + j;
+          cnt = c[j];
+          s_pick[1] = ab;
+        }
+        if (!found) ab += c[j];
+      }
+      s_pick[0] = digit;
+      s_pick[2] = cnt;
     }
     __syncthreads();
     prefix |= static_cast<uint32_t>(s_pick[0]) << shift;
@@ -246,41 +279,41 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
       const uint32_t lo_mask = 0xFFFFFFFFu << hi;
 #pragma unroll
       for (int i = 0; i < kItems; ++i)
-        if (base + i * 64 + lane < len && (key[i] & lo_mask) == prefix) s_pick[3] = static_cast<int>(key[i]);
+        if (e0 + i < len && (key[i] & lo_mask) == prefix) s_pick[3] = static_cast<int>(key[i]);
       __syncthreads();
       prefix = static_cast<uint32_t>(s_pick[3]);
       hi = 0;  // remaining is 1 here: the key itself is taken
     }
   }
-  int gt = 0, eq = 0;
+  // keys above the threshold (low half-word) and equal to it (high half-word) in this thread
+  int mine = 0;
 #pragma unroll
   for (int i = 0; i < kItems; ++i) {
-    gt += popc64(__ballot(key[i] > prefix));
-    eq += popc64(__ballot(key[i] == prefix));
+    const bool valid = e0 + i < len;
+    mine += (valid && key[i] > prefix ? 1 : 0) + (valid && key[i] == prefix ? 1 << 16 : 0);
   }
-  if (lane == 0) {
-    s_gt[wave] = gt;
-    s_eq[wave] = eq;
+  int incl = mine;  // inclusive prefix sum over the lanes below
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int v = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += v;
   }
+  __syncthreads();  // s_wave_sum is free again
+  if (lane == 63) s_wave_sum[wave] = incl;
   __syncthreads();
-  int out_run = 0, eq_run = 0;  // kept keys / threshold keys in the waves before this one
-  for (int w = 0; w < wave; ++w) {
-    const int take = min(s_eq[w], max(remaining - eq_run, 0));
-    out_run += s_gt[w] + take;
-    eq_run += s_eq[w];
-  }
+  int before = incl - mine;
+  for (int w = 0; w < wave; ++w) before += s_wave_sum[w];
+  const int gt_before = before & 0xFFFF;
+  int eq_run = before >> 16;                       // threshold keys at lower indices
+  int at = gt_before + min(eq_run, remaining);     // kept keys at lower indices
 #pragma unroll
   for (int i = 0; i < kItems; ++i) {
-    const int e = base + i * 64 + lane;
-    const uint32_t kv = key[i];
-    const bool is_eq = kv == prefix;  // padding keys are 0 < prefix
-    const uint64_t beq = __ballot(is_eq);
-    const bool kept = kv > prefix || (is_eq && eq_run + popc64(beq & lt_mask) < remaining);
-    const uint64_t bk = __ballot(kept);
-    const int at = out_run + popc64(bk & lt_mask);
-    if (kept && at < k) out[at] = start + e;
-    out_run += popc64(bk);
-    eq_run += popc64(beq);
+    const bool valid = e0 + i < len;
+    const bool is_eq = valid && key[i] == prefix;
+    const bool kept = valid && (key[i] > prefix || (is_eq && eq_run < remaining));
+    if (kept && at < k) out[at] = start + e0 + i;
+    at += kept ? 1 : 0;
+    eq_run += is_eq ? 1 : 0;
   }
 }
 
