@@ -24,7 +24,7 @@ import oracle as orc
 import paper_2601_04359_amd as pk
 from paper_2601_04359_amd import synth
 
-from test_gpu_parity import BAND, DEV, check_selection, dev, host
+from test_gpu_parity import BAND, DEV, LN2, check_selection, dev, host, q_fold
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
@@ -43,8 +43,8 @@ def _budgets(w, gamma):
 @pytest.mark.parametrize("frame", [2, 12, 24, 48])
 def test_full_size_frame(frame, fold):
     w = synth.config2(seed=1000, n_past=frame - 1)
-    q_scale = pk.folded_q_scale(w.scale) if fold else 1.0
-    scale = pk.PC_SCALE_FOLDED if fold else w.scale
+    q_scale = q_fold(w.scale) if fold else 1.0
+    scale = LN2 if fold else w.scale
     Hq, Hkv, Nk, Nq = w.Hq, w.Hkv, w.Nk, w.Nq
     newest = w.segments[-1]
     a, n_new = newest[0], newest[1]
@@ -143,7 +143,7 @@ def test_rolling_steps_at_full_frame_size():
     rnd = orc.round_to_bf16
     aK = rnd(orc.rope3d(case.anchor_K, case.anchor_pos, case.sections, case.base))
     frames = [(rnd(orc.rope3d(K, p, case.sections, case.base)), V, p) for K, V, p in case.frames]
-    q_scale, scale = pk.folded_q_scale(case.scale), pk.PC_SCALE_FOLDED   # the form bench.py's rollout runs
+    q_scale, scale = q_fold(case.scale), LN2   # the form bench.py's rollout runs
     queries = [rnd(orc.rope3d(Q, p, case.sections, case.base) * q_scale)
                for Q, p in zip(case.queries, case.query_pos)]
     n, Hkv = case.n_frame, case.Hkv

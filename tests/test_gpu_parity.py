@@ -39,6 +39,15 @@ def budgets_for(w, gamma=None, b_min=None):
     return pk.segment_budgets(w.segments, b)
 
 
+# The folded-scale form, written out here rather than taken from the package: queries carry
+# scale * log2(e) = scale / ln 2 and the calls get ln 2 as their scale.
+LN2 = float(np.log(2.0))
+
+
+def q_fold(scale: float) -> float:
+    return float(scale) / LN2
+
+
 def check_selection(idx_gpu, sc_oracle, segments, budgets, band=BAND, other_input=None):
     """idx_gpu [Hsel][Nk_out] int; sc_oracle [Hsel][Nk] fp64.  Returns #exempted keys.
     other_input [Hsel][Nk] bool marks keys whose device input bits differ from the oracle's
@@ -98,7 +107,7 @@ def test_rope3d_out_scale_is_applied_before_the_one_rounding(dtype):
     if dtype == "bf16":
         x = synth.to_bf16(x)
     pos = np.stack([rng.integers(0, 450, 300), rng.integers(0, 380, 300), rng.integers(0, 670, 300)], 1).astype(np.int32)
-    s = pk.folded_q_scale(128 ** -0.5)
+    s = q_fold(128 ** -0.5)
     want = orc.rope3d(x, pos, (32, 48, 48), 1e4) * s
     xd = dev(x, dtype)
     pk.pc_rope3d(xd, dev(pos, None), (32, 48, 48), 1e4, out_scale=s)
@@ -141,7 +150,7 @@ def _fold(Q, scale):
     """Queries that carry scale * log2(e) (rounded to bf16 once, as a rotation with out_scale
     would leave them) and the scale that is left for the calls: the same softmax, and both
     sides read the same bits."""
-    return synth.to_bf16((Q.astype(np.float64) * pk.folded_q_scale(scale)).astype(np.float32)), pk.PC_SCALE_FOLDED
+    return synth.to_bf16((Q.astype(np.float64) * q_fold(scale)).astype(np.float32)), LN2
 
 
 def _attn_check(dtype, Q, K, V, scale, fold=False):

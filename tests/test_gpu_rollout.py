@@ -12,7 +12,7 @@ import paper_2601_04359_amd as pk
 from paper_2601_04359_amd import synth
 from paper_2601_04359_amd.rollout import RollingLayer
 
-from test_gpu_parity import DEV, dev, host
+from test_gpu_parity import DEV, LN2, dev, host, q_fold
 
 pytestmark = pytest.mark.gpu
 
@@ -52,9 +52,9 @@ def _insert(layer, K, V, p, kind, frame):
     ("pow", 0.85, 32, False, True), ("norm", 0.7, 20, True, True), ("dense", 1.0, 0, False, True)])
 def test_rolling_layer_matches_oracle(mode, gamma, b_min, share, fold):
     case = synth.rolling_case(seed=11, n_steps=6)
-    aK, frames, queries = _rotated(case, pk.folded_q_scale(case.scale) if fold else 1.0)
+    aK, frames, queries = _rotated(case, q_fold(case.scale) if fold else 1.0)
     want = orc.rolling_rollout(aK, case.anchor_V, case.anchor_pos, case.anchor_segments, frames, queries,
-                               pk.PC_SCALE_FOLDED if fold else case.scale, _budget_fn(mode, case, gamma, b_min),
+                               LN2 if fold else case.scale, _budget_fn(mode, case, gamma, b_min),
                                score_rows=case.score_rows, share_heads=share)
     n = case.n_frame
     layer = RollingLayer(case.Hq, case.Hkv, case.D, case.anchor_K.shape[1] + len(frames) * n, n, case.scale,
@@ -88,9 +88,9 @@ def test_rolling_layer_with_the_steps_own_frame_in_the_cache(mode, gamma, b_min,
     inside a frame is bidirectional) and becomes the newest past frame at the next step by a
     table edit; against the oracle's rollout with include_self."""
     case = synth.rolling_case(seed=17, n_steps=5)
-    aK, frames, queries = _rotated(case, pk.folded_q_scale(case.scale) if fold else 1.0)
+    aK, frames, queries = _rotated(case, q_fold(case.scale) if fold else 1.0)
     want = orc.rolling_rollout(aK, case.anchor_V, case.anchor_pos, case.anchor_segments, frames, queries,
-                               pk.PC_SCALE_FOLDED if fold else case.scale, _budget_fn(mode, case, gamma, b_min),
+                               LN2 if fold else case.scale, _budget_fn(mode, case, gamma, b_min),
                                score_rows=case.score_rows, share_heads=share, include_self=True)
     n = case.n_frame
     layer = RollingLayer(case.Hq, case.Hkv, case.D, case.anchor_K.shape[1] + (len(frames) + 1) * n, n, case.scale,

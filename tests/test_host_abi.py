@@ -205,6 +205,17 @@ def test_batched_compaction_and_mask_argument_checks(L):
     assert L.pc_strerror(-8) not in (None, L.pc_strerror(-7))
 
 
+def test_fold_helpers_are_the_constants_the_header_names():
+    import math
+    assert pk.PC_SCALE_FOLDED == math.log(2.0)
+    # what the kernels test for: float(ln 2) * float(log2 e), rounded to fp32, is exactly 1
+    assert C.c_float(C.c_float(pk.PC_SCALE_FOLDED).value * C.c_float(1.4426950408889634).value).value == 1.0
+    for s in (128 ** -0.5, 64 ** -0.5, 0.3):
+        assert abs(pk.folded_q_scale(s) - s / math.log(2.0)) <= 1e-15 * s
+    src = open(os.path.join(ROOT, "include", "packcache.h")).read()
+    assert "#define PC_SCALE_FOLDED 0.693147180559945309f" in src
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess
     import sys
