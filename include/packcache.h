@@ -156,6 +156,11 @@ int pc_rebase(void* K, int dtype, int Hkv, int D, int64_t k_stride_h, int32_t* p
  *   scale  > 0, the softmax scale of Eq. 2 (1/sqrt(D)).  scale = PC_SCALE_FOLDED (ln 2) with
  *          queries that carry scale * log2(e) (see pc_rope3d) is the same computation and takes
  *          the bf16 kernels' shorter loop; lse stays the natural-log sum-exp of the logits.
+ *   key_begin, key_end   only keys [key_begin, key_end) get a score (key_end = 0: up to Nk);
+ *          entries of `score` outside the range are not written.  Every key still counts in
+ *          every query's softmax normaliser.  For callers that know which rows can be pruned at
+ *          all (anchors never are; a frame that already sits at its budget is not either) and do
+ *          not want to pay for scores nobody reads.
  * Summation order is fixed (no atomics): results are bit-reproducible.
  * Errors: PC_ERR_NULL, PC_ERR_DTYPE, PC_ERR_SHAPE, PC_ERR_UNSUPPORTED, PC_ERR_WORKSPACE,
  * PC_ERR_HIP.
@@ -164,7 +169,7 @@ size_t pc_score_workspace_bytes(int Hq, int Hkv, int n_qs, int Nk, int share_hea
 int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hkv, int n_qs, int Nk,
              int D, int64_t q_stride_h, int64_t k_stride_h, const int32_t* q_rows, float scale,
              const float* lse, int64_t lse_stride_h, float* score, int64_t score_stride_h,
-             int share_heads, void* ws, size_t ws_bytes, void* stream);
+             int share_heads, int key_begin, int key_end, void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
  * pc_compact_plan -- host half of compaction: the segment table and key count after

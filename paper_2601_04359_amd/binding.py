@@ -73,7 +73,7 @@ def lib() -> C.CDLL:
         L.pc_score_workspace_bytes.restype = sz
         L.pc_score_workspace_bytes.argtypes = [C.c_int] * 5
         L.pc_score.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i64, i64, vp,
-                               C.c_float, vp, i64, vp, i64, C.c_int, vp, sz, vp]
+                               C.c_float, vp, i64, vp, i64, C.c_int, C.c_int, C.c_int, vp, sz, vp]
         L.pc_compact_batch_workspace_bytes.restype = sz
         L.pc_compact_batch_workspace_bytes.argtypes = [C.c_int] * 4
         L.pc_compact_batch.argtypes = [C.c_int, vp, vp, vp, C.c_int, C.c_int, C.c_int, i64, i64, i64, i64, vp, i64,
@@ -186,10 +186,11 @@ def pc_score_workspace_bytes(Hq: int, Hkv: int, n_qs: int, Nk: int, share_heads:
 
 
 def pc_score(Qs, K, Nk: int, scale: float, lse=None, score=None, share_heads: bool = False, ws=None,
-             q_rows=None):
+             q_rows=None, key_range=None):
     """Qs [Hq][rows][D], K [Hkv][>=Nk][D] -> score fp32 [Hsel][Nk].  q_rows (int32, device)
     picks the rows of Qs that score; None: all of them.  lse (fp32 [Hq][rows], optional) is
-    indexed like the rows of Qs."""
+    indexed like the rows of Qs.  key_range = (begin, end): only these keys get a score (all of
+    them still count in the softmax); the rest of `score` is left as it is."""
     import torch
     Hq, n_qs, D = Qs.shape
     if q_rows is not None:
@@ -205,7 +206,8 @@ def pc_score(Qs, K, Nk: int, scale: float, lse=None, score=None, share_heads: bo
     _check(lib().pc_score(Qs.data_ptr(), K.data_ptr(), _dtype_code(K), Hq, Hkv, n_qs, Nk, D, Qs.stride(0),
                           K.stride(0), _ptr(q_rows), float(scale), _ptr(lse), 0 if lse is None else lse.stride(0),
                           score.data_ptr(), score.stride(0),
-                          int(share_heads), ws.data_ptr(), ws.numel(), _stream()))
+                          int(share_heads), 0 if key_range is None else int(key_range[0]),
+                          0 if key_range is None else int(key_range[1]), ws.data_ptr(), ws.numel(), _stream()))
     return score
 
 

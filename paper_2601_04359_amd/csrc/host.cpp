@@ -183,7 +183,7 @@ extern "C" const char* pc_strerror(int status) {
 
 extern "C" const char* pc_last_error_detail(void) { return g_detail; }
 
-extern "C" int pc_version(void) { return 103; }
+extern "C" int pc_version(void) { return 104; }
 
 extern "C" int pc_budget(int mode, int n_frame_tokens, int n_past, double gamma, int b_min,
                          int32_t* budget_out) {

@@ -603,7 +603,7 @@ extern "C" size_t pc_score_workspace_bytes(int Hq, int Hkv, int n_qs, int Nk, in
 extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hkv, int n_qs,
                         int Nk, int D, int64_t q_stride_h, int64_t k_stride_h,
                         const int32_t* q_rows, float scale, const float* lse, int64_t lse_stride_h, float* score,
-                        int64_t score_stride_h, int share_heads,
+                        int64_t score_stride_h, int share_heads, int key_begin, int key_end,
                         void* ws, size_t ws_bytes, void* stream) {
   PC_REQUIRE(dtype == PC_F32 || dtype == PC_BF16, PC_ERR_DTYPE, "pc_score: dtype %d", dtype);
   PC_REQUIRE(Hq > 0 && Hkv > 0 && Hq % Hkv == 0, PC_ERR_SHAPE,
@@ -616,6 +616,12 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
              PC_ERR_SHAPE, "pc_score: a head stride is smaller than rows*D");
   PC_REQUIRE(share_heads || Hkv == 1 || score_stride_h >= Nk, PC_ERR_SHAPE,
              "pc_score: score head stride %lld < Nk", static_cast<long long>(score_stride_h));
+  if (key_end <= 0) key_end = Nk;  // 0: up to the last key
+  PC_REQUIRE(key_begin >= 0 && key_begin < key_end && key_end <= Nk, PC_ERR_SHAPE,
+             "pc_score: key range [%d, %d) outside [0, %d)", key_begin, key_end, Nk);
+  // Keys outside the range take part in every normaliser (pass 1 runs over all Nk keys) but get no
+  // score: pass 2 simply runs on the sub-range (pointers and counts offset here).
+  const int nkr = key_end - key_begin;
   PC_REQUIRE(lse == nullptr || Hq == 1 || lse_stride_h >= n_qs, PC_ERR_SHAPE,
              "pc_score: lse head stride %lld < n_qs", static_cast<long long>(lse_stride_h));
   const WsLayout lay = ws_layout(Hq, Hkv, n_qs, Nk, share_heads);
@@ -660,26 +666,28 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
                                                                  -1.4426950408889634f, -INFINITY);
       PC_CHECK_LAUNCH("pc_score lse import");
     }
-    const int n_key_blocks = ceil_div(Nk, kBlockRows);
+    const int n_key_blocks = ceil_div(nkr, kBlockRows);
     const int n_qsplits = choose_splits(n_key_blocks * Hkv, rep * (n_pad / kTileRows), kMaxQSplits);
     const bool direct = n_qsplits == 1 && !share_heads;
+    float* score_r = score + key_begin;
     col_kernel<<<n_key_blocks * Hkv * n_qsplits, kThreads, kColSmem, s>>>(
-        static_cast<const uint16_t*>(Qs), q_rows, static_cast<const uint16_t*>(K), ws_lse, direct ? score : ws_col,
-        direct ? score_stride_h : Nk, static_cast<int64_t>(Hkv) * Nk, Hkv, rep, n_qs, Nk, q_stride_h, k_stride_h, c,
-        n_key_blocks, n_qsplits);
+        static_cast<const uint16_t*>(Qs), q_rows, static_cast<const uint16_t*>(K) + static_cast<int64_t>(key_begin) * kD,
+        ws_lse, direct ? score_r : ws_col, direct ? score_stride_h : nkr, static_cast<int64_t>(Hkv) * nkr, Hkv, rep,
+        n_qs, nkr, q_stride_h, k_stride_h, c, n_key_blocks, n_qsplits);
     PC_CHECK_LAUNCH("pc_score column pass");
     if (!direct) {
-      score_reduce<<<dim3(ceil_div(Nk, 256), share_heads ? 1 : Hkv), 256, 0, s>>>(ws_col, score, score_stride_h,
-                                                                                  n_qsplits, Hkv, Nk, share_heads);
+      score_reduce<<<dim3(ceil_div(nkr, 256), share_heads ? 1 : Hkv), 256, 0, s>>>(ws_col, score_r, score_stride_h,
+                                                                                   n_qsplits, Hkv, nkr, share_heads);
       PC_CHECK_LAUNCH("pc_score reduce");
     }
     return PC_OK;
   } else {
     PC_REQUIRE(D == 64 || D == 128, PC_ERR_UNSUPPORTED, "pc_score: fp32 tier needs D=64 or 128, got %d", D);
-    float* per_head = share_heads ? ws_col : score;
-    const int64_t per_head_stride = share_heads ? Nk : score_stride_h;
+    float* per_head = share_heads ? ws_col : score + key_begin;
+    const int64_t per_head_stride = share_heads ? nkr : score_stride_h;
     const float* q = static_cast<const float*>(Qs);
     const float* k = static_cast<const float*>(K);
+    const float* k_r = k + static_cast<int64_t>(key_begin) * D;
     const float* lse_in = ws_lse;
     if (lse != nullptr) {
       score_import_lse<<<ceil_div(Hq * n_qs, 256), 256, 0, s>>>(lse, lse_stride_h, q_rows, ws_lse, Hq, n_qs, n_qs, 1.f,
@@ -693,16 +701,16 @@ extern "C" int pc_score(const void* Qs, const void* K, int dtype, int Hq, int Hk
         score_rowpass_f32<128><<<grid, 64, 0, s>>>(q, q_rows, k, ws_lse, rep, n_qs, Nk, q_stride_h, k_stride_h, scale);
       PC_CHECK_LAUNCH("pc_score row pass");
     }
-    const dim3 grid(ceil_div(Nk, 64), Hkv);
+    const dim3 grid(ceil_div(nkr, 64), Hkv);
     if (D == 64)
-      score_colpass_f32<64><<<grid, 64, 0, s>>>(q, q_rows, k, lse_in, per_head, per_head_stride, rep, n_qs, Nk,
+      score_colpass_f32<64><<<grid, 64, 0, s>>>(q, q_rows, k_r, lse_in, per_head, per_head_stride, rep, n_qs, nkr,
                                                   q_stride_h, k_stride_h, scale);
     else
-      score_colpass_f32<128><<<grid, 64, 0, s>>>(q, q_rows, k, lse_in, per_head, per_head_stride, rep, n_qs, Nk,
+      score_colpass_f32<128><<<grid, 64, 0, s>>>(q, q_rows, k_r, lse_in, per_head, per_head_stride, rep, n_qs, nkr,
                                                    q_stride_h, k_stride_h, scale);
     PC_CHECK_LAUNCH("pc_score column pass");
     if (share_heads) {
-      score_reduce<<<ceil_div(Nk, 256), 256, 0, s>>>(ws_col, score, score_stride_h, 1, Hkv, Nk, 1);
+      score_reduce<<<ceil_div(nkr, 256), 256, 0, s>>>(ws_col, score + key_begin, score_stride_h, 1, Hkv, nkr, 1);
       PC_CHECK_LAUNCH("pc_score head sum");
     }
   }

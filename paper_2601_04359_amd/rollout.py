@@ -142,8 +142,12 @@ class RollingLayer:
         budgets = self.budgets()
         if all(b >= s[1] for s, b in zip(self.segments, budgets) if s[2] == pk.PC_SEG_FRAME):
             return   # every frame is within its budget: nothing to score, nothing to move
+        # only segments that lose rows at this step need scores (anchors never do, a frame that sits at
+        # its budget does not either): the scoring covers the span from the first to the last of them
+        prunable = [s for s, b in zip(self.segments, budgets) if s[2] == pk.PC_SEG_FRAME and b < s[1]]
+        span = (prunable[0][0], prunable[-1][0] + prunable[-1][1])
         pk.pc_score(Q, self.K, self.nk, self.call_scale, lse=lse, score=self.score, share_heads=self.share_heads,
-                    ws=self._ws_score, q_rows=self.q_rows)
+                    ws=self._ws_score, q_rows=self.q_rows, key_range=span)
         self.segments, self.nk = pk.pc_compact(self.K, self.V, self.pos, self.score, self.segments,
                                                budgets, share_heads=self.share_heads, ws=self._ws_compact)
 

@@ -357,6 +357,22 @@ def test_score_row_index_equals_gathered_rows():
         assert np.all(np.abs(host(a) - want) <= 2e-7 + 2e-5 * want)
 
 
+@pytest.mark.parametrize("share", [False, True])
+@pytest.mark.parametrize("case", ["mid", "c1"])
+def test_score_key_range_scores_only_the_range(case, share):
+    # keys outside the range count in every normaliser but get no score: inside, the bits of the
+    # full call; outside, whatever the buffer held
+    w = synth.midsize() if case == "mid" else synth.config1()
+    Q, K = dev(w.Q, w.dtype), dev(w.K, w.dtype)
+    rows = dev(w.score_rows.astype(np.int32), None)
+    full = pk.pc_score(Q, K, w.Nk, w.scale, q_rows=rows, share_heads=share)
+    for a, b in ((0, w.Nk), (w.segments[1][0], w.Nk), (w.segments[2][0] + 3, w.Nk - 5), (17, 18)):
+        part = torch.full_like(full, -7.0)
+        pk.pc_score(Q, K, w.Nk, w.scale, q_rows=rows, share_heads=share, score=part, key_range=(a, b))
+        assert torch.equal(part[:, a:b], full[:, a:b]), (a, b)
+        assert torch.all(part[:, :a] == -7.0) and torch.all(part[:, b:] == -7.0)
+
+
 def test_score_is_bit_reproducible():
     w = synth.midsize()
     Qs, K = dev(w.Q[:, w.score_rows], "bf16"), dev(w.K, "bf16")

@@ -143,8 +143,11 @@ def test_argument_validation_returns_before_any_device_work(L):
     # score: workspace missing / too small
     need = L.pc_score_workspace_bytes(4, 2, 8, 100, 0)
     assert need > 0
-    assert L.pc_score(one, one, 1, 4, 2, 8, 100, 128, 1024, 12800, None, 0.1, None, 0, one, 100, 0, None, 0, None) == -6
-    assert L.pc_score(one, one, 1, 4, 2, 8, 100, 128, 1024, 12800, None, 0.1, None, 0, one, 100, 0, one, need - 1, None) == -6
+    assert L.pc_score(one, one, 1, 4, 2, 8, 100, 128, 1024, 12800, None, 0.1, None, 0, one, 100, 0, 0, 0, None, 0, None) == -6
+    assert L.pc_score(one, one, 1, 4, 2, 8, 100, 128, 1024, 12800, None, 0.1, None, 0, one, 100, 0, 0, 0, one, need - 1, None) == -6
+    # key range: empty, reversed or past the end
+    for kb, ke in ((5, 5), (7, 3), (0, 101), (-1, 10), (100, 0)):
+        assert L.pc_score(one, one, 1, 4, 2, 8, 100, 128, 1024, 12800, None, 0.1, None, 0, one, 100, 0, kb, ke, one, need, None) == -2
     # compact: too many segments; partial aliasing of outputs
     seg = (binding.pc_segment * 2)(binding.pc_segment(0, 4, 0, 0), binding.pc_segment(4, 8, 2, 1))
     bud = (C.c_int32 * 2)(4, 3)
