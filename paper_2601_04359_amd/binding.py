@@ -275,10 +275,13 @@ def pc_compact_batch_workspace_bytes(n_layers: int, Hkv: int, Nk_in: int, share_
     return lib().pc_compact_batch_workspace_bytes(n_layers, Hkv, Nk_in, int(share_heads))
 
 
-def pc_compact_batch(K, V, pos, score, segments, budgets, share_heads: bool = False, out=None, idx=None, ws=None):
+def pc_compact_batch(K, V, pos, score, segments, budgets, share_heads: bool = False, out=None, idx=None, ws=None,
+                     phases: int = 3, stream=None):
     """pc_compact over a stack of layers in one call: K, V [L][Hkv][cap][D], pos int32
     [L][Hsel][cap][3], score fp32 [L][Hsel][>=Nk]; out / idx as in pc_compact with a leading
-    layer axis.  Returns (segments_out, Nk_out)."""
+    layer axis.  phases: PC_COMPACT_SELECT, PC_COMPACT_GATHER or both (the two halves of
+    pc_compact_batch_phase, for callers that overlap them on two streams; pass the same ws to
+    both); stream: a torch stream (default: the current one).  Returns (segments_out, Nk_out)."""
     L, Hkv, _, D = K.shape
     _rows_dense(K, "K")
     _rows_dense(V, "V")
@@ -290,13 +293,14 @@ def pc_compact_batch(K, V, pos, score, segments, budgets, share_heads: bool = Fa
     Ko, Vo, po = (K, V, pos) if out is None else out
     if ws is None:
         ws = _workspace(pc_compact_batch_workspace_bytes(L, Hkv, nk_in, share_heads), K)
-    _check(lib().pc_compact_batch(L, K.data_ptr(), V.data_ptr(), pos.data_ptr(), _dtype_code(K), Hkv, D,
-                                  K.stride(1), K.stride(0), pos.stride(1), pos.stride(0), score.data_ptr(),
-                                  score.stride(1), score.stride(0), _seg_array(segments), n, b, int(share_heads),
-                                  Ko.data_ptr(), Vo.data_ptr(), po.data_ptr(), Ko.stride(1), Ko.stride(0),
-                                  po.stride(1), po.stride(0), _ptr(idx), 0 if idx is None else idx.stride(1),
-                                  0 if idx is None else idx.stride(0), seg_out, C.byref(nk), ws.data_ptr(),
-                                  ws.numel(), _stream()))
+    _check(lib().pc_compact_batch_phase(int(phases), L, K.data_ptr(), V.data_ptr(), pos.data_ptr(), _dtype_code(K),
+                                        Hkv, D, K.stride(1), K.stride(0), pos.stride(1), pos.stride(0),
+                                        score.data_ptr(), score.stride(1), score.stride(0), _seg_array(segments), n, b,
+                                        int(share_heads), Ko.data_ptr(), Vo.data_ptr(), po.data_ptr(), Ko.stride(1),
+                                        Ko.stride(0), po.stride(1), po.stride(0), _ptr(idx),
+                                        0 if idx is None else idx.stride(1), 0 if idx is None else idx.stride(0),
+                                        seg_out, C.byref(nk), ws.data_ptr(), ws.numel(),
+                                        _stream() if stream is None else stream.cuda_stream))
     return [(s.start, s.len, s.kind, s.frame) for s in seg_out[:n]], nk.value
 
 
