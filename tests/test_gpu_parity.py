@@ -667,6 +667,32 @@ def test_select_and_gather_as_two_calls_on_two_streams(in_place):
     assert np.array_equal(host(po[:, :nk]), ref[2])
 
 
+def test_batch_halves_on_two_streams_equal_the_single_batched_call():
+    # a stack of three layers: select half on a side stream, gather half on the main stream
+    w = synth.midsize()
+    L = 3
+    rng = np.random.default_rng(21)
+    K = torch.stack([dev(synth.to_bf16(rng.standard_normal(w.K.shape).astype(np.float32)), "bf16") for _ in range(L)])
+    V = torch.stack([dev(synth.to_bf16(rng.standard_normal(w.V.shape).astype(np.float32)), "bf16") for _ in range(L)])
+    pos = dev(np.broadcast_to(w.pos_k[None, None], (L, w.Hkv, w.Nk, 3)).copy(), None)
+    sc = torch.rand((L, w.Hkv, w.Nk), device=DEV)
+    budgets = budgets_for(w)
+    K1, V1, p1 = K.clone(), V.clone(), pos.clone()
+    segs1, nk1 = pk.pc_compact_batch(K1, V1, p1, sc, w.segments, budgets)
+    ws = torch.empty(pk.pc_compact_batch_workspace_bytes(L, w.Hkv, w.Nk), dtype=torch.uint8, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    pk.pc_compact_batch(K, V, pos, sc, w.segments, budgets, ws=ws, phases=pk.PC_COMPACT_SELECT, stream=side)
+    done = torch.cuda.Event()
+    done.record(side)
+    torch.cuda.current_stream().wait_event(done)
+    segs2, nk2 = pk.pc_compact_batch(K, V, pos, sc, w.segments, budgets, ws=ws, phases=pk.PC_COMPACT_GATHER)
+    torch.cuda.synchronize()
+    assert segs1 == segs2 and nk1 == nk2
+    assert torch.equal(K[:, :, :nk1], K1[:, :, :nk1]) and torch.equal(V[:, :, :nk1], V1[:, :, :nk1])
+    assert torch.equal(pos[:, :, :nk1], p1[:, :, :nk1])
+
+
 def test_random_shapes_attention_score_compaction():
     # a seeded walk over ragged shapes and head groupings: every call against the oracle
     rng = np.random.default_rng(2024)
