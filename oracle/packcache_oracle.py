@@ -206,17 +206,24 @@ def frame_attn(Q, K, V, scale: float, keep: np.ndarray | None = None):
     return O, L
 
 
-def score(Qs, K, scale: float, share_heads: bool = False) -> np.ndarray:
+def score(Qs, K, scale: float, share_heads: bool = False, valid=None) -> np.ndarray:
     """Importance of every cached key: the softmax probability it receives, summed
     over the scoring queries and over the query heads of its KV group.
     The softmax runs over ALL keys presented (anchors included).
+    valid ([Nk] bool, the cache mask of Sec. 3.1 / Eq. 1, one flag per token for all heads):
+    a masked key is ignored in attention, i.e. its logit is -inf: it receives no probability
+    and does not count in any query's normaliser.  The same result as deleting the masked
+    keys first (which is what the cache does with them, Sec. 3.4) and scoring the rest.
     Returns [Hkv][Nk], or [1][Nk] (summed over KV heads too) when share_heads."""
     Qs, K = f64(Qs), f64(K)
     hq, hkv = Qs.shape[0], K.shape[0]
     rep = hq // hkv
     out = np.zeros((hkv, K.shape[1]))
     for h in range(hq):
-        p, _ = softmax_rows(logits(Qs[h], K[h // rep], scale))
+        s = logits(Qs[h], K[h // rep], scale)
+        if valid is not None:
+            s = np.where(np.asarray(valid, dtype=bool)[None, :], s, -np.inf)
+        p, _ = softmax_rows(s)
         out[h // rep] += p.sum(axis=0)
     return out.sum(axis=0, keepdims=True) if share_heads else out
 

@@ -602,3 +602,26 @@ def test_cache_mask_never_keeps_a_masked_token_and_equals_deleting_them_first():
     full = orc.compact(w.K, w.V, w.pos_k[None], sc, w.segments, budgets, valid=np.ones(w.Nk, bool))
     base = orc.compact(w.K, w.V, w.pos_k[None], sc, w.segments, budgets)
     assert np.array_equal(full[3], base[3]) and full[4] == base[4]
+
+
+def test_masked_keys_leave_the_scoring_softmax_and_equal_deleting_them_first():
+    # Sec. 3.1, the sentence after Eq. 1: masked entries are ignored in attention.  A masked key
+    # gets no probability and does not count in any normaliser: scoring with the mask is scoring
+    # the cache with those keys deleted (what Sec. 3.4 does with them physically).
+    w = synth.config1()
+    rng = np.random.default_rng(9)
+    valid = rng.random(w.Nk) < 0.6
+    valid[:3] = [False, True, False]
+    got = orc.score(w.Q, w.K, w.scale, valid=valid)
+    rows = np.flatnonzero(valid)
+    deleted_first = orc.score(w.Q, w.K[:, rows], w.scale)
+    np.testing.assert_allclose(got[:, rows], deleted_first, rtol=0, atol=1e-13)
+    assert np.all(got[:, ~valid] == 0.0)
+    # total mass is still one per scoring query and query head (rows of the softmax sum to 1)
+    np.testing.assert_allclose(got.sum(axis=1), w.Q.shape[1] * (w.Hq // w.Hkv), rtol=1e-12)
+    # brute force over the kept keys only
+    np.testing.assert_allclose(deleted_first, orc.score_bruteforce(w.Q, w.K[:, rows], w.scale), rtol=0, atol=1e-12)
+    # an all-ones mask is no mask
+    assert np.array_equal(orc.score(w.Q, w.K, w.scale, valid=np.ones(w.Nk, bool)), orc.score(w.Q, w.K, w.scale))
+    # and the unmasked normaliser is NOT the masked one: the mask matters
+    assert np.abs(orc.score(w.Q, w.K, w.scale)[:, rows] - deleted_first).max() > 1e-3
