@@ -124,6 +124,29 @@ def _rows_dense(t, name: str) -> None:
         raise PackCacheError(-2, f"{name}: rows must be dense with the last dimension contiguous")
 
 
+def _check_kv_layout(K, V, pos, out, share_heads: bool, layer_axis: bool = False) -> None:
+    """The compaction calls take ONE head (and layer) stride for K and V and one for pos: refuse
+    tensors whose strides differ, whose rows are not dense, or whose pos is not [..][Hsel][cap][3]."""
+    _rows_dense(K, "K")
+    _rows_dense(V, "V")
+    lead = 2 if layer_axis else 1
+    if V.shape != K.shape or V.stride()[:lead] != K.stride()[:lead]:
+        raise PackCacheError(-2, "K and V must have the same shape and the same head / layer strides")
+    _rows_dense(pos, "pos")
+    hsel = 1 if share_heads else K.shape[lead - 1]
+    if pos.shape[-1] != 3 or pos.shape[lead - 1] != hsel:
+        raise PackCacheError(-2, f"pos must be int32 [..][{hsel}][cap][3], got {tuple(pos.shape)}")
+    if out is not None:
+        Ko, Vo, po = out
+        _rows_dense(Ko, "K_out")
+        _rows_dense(Vo, "V_out")
+        _rows_dense(po, "pos_out")
+        if Vo.shape != Ko.shape or Vo.stride()[:lead] != Ko.stride()[:lead]:
+            raise PackCacheError(-2, "K_out and V_out must have the same shape and the same head / layer strides")
+        if po.shape[-1] != 3 or po.shape[lead - 1] != hsel:
+            raise PackCacheError(-2, f"pos_out must be int32 [..][{hsel}][cap][3], got {tuple(po.shape)}")
+
+
 def _workspace(nbytes: int, like):
     import torch
     return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=like.device)
@@ -252,8 +275,7 @@ def pc_compact(K, V, pos, score, segments, budgets, share_heads: bool = False, o
     """Select and compact.  out = None compacts in place; out = (K_out, V_out, pos_out)
     writes there.  Returns (segments_out, Nk_out)."""
     Hkv, _, D = K.shape
-    _rows_dense(K, "K")
-    _rows_dense(V, "V")
+    _check_kv_layout(K, V, pos, out, share_heads)
     n = len(segments)
     nk_in = segments[-1][0] + segments[-1][1] if n else 0
     seg_in = _seg_array(segments)
@@ -283,8 +305,12 @@ def pc_compact_batch(K, V, pos, score, segments, budgets, share_heads: bool = Fa
     pc_compact_batch_phase, for callers that overlap them on two streams; pass the same ws to
     both); stream: a torch stream (default: the current one).  Returns (segments_out, Nk_out)."""
     L, Hkv, _, D = K.shape
-    _rows_dense(K, "K")
-    _rows_dense(V, "V")
+    _check_kv_layout(K, V, pos, out, share_heads, layer_axis=True)
+    if ws is None and (int(phases) != 3 or stream is not None):
+        # a workspace made here would be a fresh, uninitialised one per call (the GATHER half needs
+        # the one its SELECT half filled) and would go back to the allocator of the CURRENT stream
+        # while another stream's kernels may still be using it
+        raise PackCacheError(-6, "pc_compact_batch: pass ws when phases != 3 or a stream is given")
     n = len(segments)
     nk_in = segments[-1][0] + segments[-1][1] if n else 0
     seg_out = (pc_segment * max(n, 1))()
@@ -311,6 +337,7 @@ def pc_compact_prepared(K, V, pos, score, segments, budgets, ws, share_heads: bo
     select half, 2 = the gather half, 3 = both; stream: a torch stream (default: the
     current one at preparation time)."""
     Hkv, _, D = K.shape
+    _check_kv_layout(K, V, pos, out, share_heads)
     n = len(segments)
     seg_in = _seg_array(segments)
     b = (C.c_int32 * max(n, 1))(*[int(v) for v in budgets])
@@ -345,6 +372,8 @@ def pc_frame_attn(Q, K, V, Nk: int, scale: float, O=None, lse=None, ws=None):
         ws = _workspace(nws, Q)
     if K.stride(0) != V.stride(0):
         raise PackCacheError(-2, "K and V must share their head stride")
+    if lse is not None and (tuple(lse.shape) != (Hq, Nq) or not lse.is_contiguous()):
+        raise PackCacheError(-2, f"lse must be a contiguous fp32 [{Hq}][{Nq}] tensor")
     _check(lib().pc_frame_attn(Q.data_ptr(), K.data_ptr(), V.data_ptr(), _dtype_code(Q), Hq, Hkv, Nq, Nk, D,
                                Q.stride(0), K.stride(0), O.stride(0), float(scale), O.data_ptr(), _ptr(lse),
                                _ptr(ws), 0 if ws is None else ws.numel(), _stream()))

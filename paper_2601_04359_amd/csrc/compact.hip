@@ -351,6 +351,13 @@ __global__ __launch_bounds__(kGatherThreads) void gather_kernel(
     if (threadIdx.x == 0) s_ticket = atomicAdd(&sync->ticket[vh][0], 1);
     __syncthreads();
     cc = s_ticket;
+    // A ticket outside the launch's chunks means the counters were not cleared by the SELECT half
+    // of this call (GATHER alone, or on another workspace): flag it and move nothing rather than
+    // index the flags with it.  Block-uniform, and before any other barrier.
+    if (cc < 0 || cc >= per_layer / Hkv) {
+      if (threadIdx.x == 0) __hip_atomic_store(&sync->abort, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return;
+    }
   }
   const int hs = share_heads ? 0 : h;
   const int r0 = cc * kRows;

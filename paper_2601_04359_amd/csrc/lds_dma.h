@@ -39,13 +39,26 @@ __device__ __forceinline__ float wave_half_swap(float v) {
 // is stored at chunk position c ^ (r & 15).  The map is an involution.
 __device__ __forceinline__ int k_chunk_pos(int row, int chunk) { return chunk ^ (row & 15); }
 
+// The LDS base of a direct load travels in M0, a register the compiler reserves for itself and
+// does not accept on a clobber list: the statements below put back what they found in it, so
+// they are neutral to whatever the compiler keeps there (two scalar moves per load).
 // One wave-wide 1-KB direct load: lane i's 16 bytes from `src` land at lds_base + 16 i.
 __device__ __forceinline__ void dma_16B(const void* src, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(src) : "memory");
+  uint32_t saved_m0;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+      : "=&s"(saved_m0)
+      : "s"(lds_base), "v"(src)
+      : "memory");
 }
 // One wave-wide 256-byte direct load: lane i's 4 bytes from `src` land at lds_base + 4 i.
 __device__ __forceinline__ void dma_4B(const void* src, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_base), "v"(src) : "memory");
+  uint32_t saved_m0;
+  asm volatile(
+      "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, off\n\ts_mov_b32 m0, %0"
+      : "=&s"(saved_m0)
+      : "s"(lds_base), "v"(src)
+      : "memory");
 }
 
 __device__ __forceinline__ bf16x8 lds_frag(const lds_u8* p) {
