@@ -88,12 +88,41 @@ class RollingLayer:
         a = self.nk
         return self.K[:, a:a + n], self.V[:, a:a + n], self.pos[:, a:a + n]
 
-    def commit(self, n: int, kind: int, frame: int, rotate_with=None) -> None:
+    def commit(self, n: int, kind: int, frame: int, rotate_with=None, valid=None) -> None:
         """Make the n reserved rows part of the cache.  rotate_with: int32 [n][3] device
-        positions; when given the new keys are rotated in place (a1) on insertion."""
+        positions; when given the new keys are rotated in place (a1) on insertion.
+        valid (host array of n flags, the cache mask of Sec. 3.1 for this frame): only the
+        unmasked tokens enter the cache.  The masked rows are removed on insertion by the
+        compaction call itself (mask as the score, budget = unmasked count; the rest of the
+        cache keeps every row), so no later scoring or attention ever sees them: masked
+        entries are ignored in attention (Sec. 3.1), and removed rather than stored (Sec. 3.4)."""
         a = self.nk
         if rotate_with is not None:
             pk.pc_rope3d(self.K[:, a:a + n], rotate_with, self.sections, self.base)
+        if valid is not None:
+            import numpy as np
+            import torch
+            if kind != pk.PC_SEG_FRAME:
+                raise ValueError("a cache mask applies to a generated frame entering the cache (PC_SEG_FRAME)")
+            v = np.ascontiguousarray(np.asarray(valid) != 0, dtype=np.uint8)
+            if v.shape != (n,):
+                raise ValueError(f"valid must hold {n} flags, got shape {v.shape}")
+            n_valid = int(v.sum())
+            if n_valid < n:
+                if not hasattr(self, "score"):      # the full-cache baseline scores nothing else
+                    self.score = torch.empty((self.pos.shape[0], self.capacity), dtype=torch.float32,
+                                             device=self.K.device)
+                    self._ws_compact = torch.empty(pk.pc_compact_workspace_bytes(self.Hkv, self.capacity,
+                                                                                 self.share_heads),
+                                                   dtype=torch.uint8, device=self.K.device)
+                sc_new = self.score[:, a:a + n]
+                sc_new.zero_()
+                pk.pc_mask_scores(sc_new, torch.from_numpy(v).to(self.K.device))    # masked -> -1 < 0
+                table = self.segments + [(a, n, kind, frame)]
+                keep = [s[1] for s in self.segments] + [n_valid]
+                self.segments, self.nk = pk.pc_compact(self.K, self.V, self.pos, self.score, table, keep,
+                                                       share_heads=self.share_heads, ws=self._ws_compact)
+                return
         self.segments.append((a, n, kind, frame))
         self.nk = a + n
 
@@ -162,3 +191,103 @@ class RollingLayer:
             pk.pc_rope3d(Q, q_pos, self.sections, self.base, out_scale=self.q_out_scale)
         self.refresh(Q)
         return self.attend(Q, O=O, lse=lse)
+
+
+class RollingStack:
+    """The packed caches of a stack of layers in one allocation, re-packed TOGETHER when a frame
+    step ends (Sec. 3.4 re-packs the cache at the frame step, not per attention call).
+
+    Per frame step:
+        reserve()/commit()   the frame generated last is appended whole to every layer's cache
+        per layer:           attend() over the cache as it stands, with the log-sum-exp of the pass;
+                             score_layer() turns that log-sum-exp into importances with ONE QK^T pass
+        repack()             budgets, then one pc_compact_batch for the whole stack
+
+    All layers share one segment table: budgets depend on the temporal distance only, so every
+    layer keeps the same COUNT of rows per frame (each its own rows).  The cache a step attends
+    over is the one the previous step packed plus the whole newest frame; the cache repack()
+    leaves is the one RollingLayer.step() would have attended over at the same step (same keys
+    scored by the same queries under the same budgets).
+    """
+
+    def __init__(self, n_layers: int, Hq: int, Hkv: int, D: int, capacity: int, n_frame: int, scale: float,
+                 mode: str = "pow", gamma: float = 0.85, b_min: int = 512, budget_tokens: int | None = None,
+                 n_score: int = 512, sections=(32, 48, 48), base: float = 10000.0, dtype=None, device="cuda:0",
+                 share_heads: bool = False, fold_scale: bool = False):
+        import torch
+        if mode not in MODES or mode == "dense":
+            raise ValueError(f"mode {mode!r} not in {sorted(m for m in MODES if m != 'dense')}")
+        self.L, self.Hq, self.Hkv, self.D, self.capacity, self.n_frame = n_layers, Hq, Hkv, D, capacity, n_frame
+        self.scale, self.mode, self.gamma, self.b_min = scale, mode, gamma, b_min
+        self.fold_scale = fold_scale
+        self.q_out_scale = pk.folded_q_scale(scale) if fold_scale else 1.0
+        self.call_scale = pk.PC_SCALE_FOLDED if fold_scale else scale
+        self.budget_tokens = n_frame if budget_tokens is None else budget_tokens
+        self.sections, self.base, self.share_heads = tuple(sections), base, share_heads
+        dtype = torch.bfloat16 if dtype is None else dtype
+        hsel = 1 if share_heads else Hkv
+        self.K = torch.empty((n_layers, Hkv, capacity, D), dtype=dtype, device=device)
+        self.V = torch.empty_like(self.K)
+        self.pos = torch.empty((n_layers, hsel, capacity, 3), dtype=torch.int32, device=device)
+        self.score = torch.empty((n_layers, hsel, capacity), dtype=torch.float32, device=device)
+        self.segments: list[tuple[int, int, int, int]] = []
+        self.nk = 0
+        n_rows = min(n_score, n_frame)
+        self.q_rows = ((torch.arange(n_rows, dtype=torch.int64) * n_frame) // n_rows).to(torch.int32).to(device)
+        self._ws_attn = torch.empty(4 * Hq * n_frame * (D * 4 + 8) + 1024, dtype=torch.uint8, device=device)
+        self._ws_score = torch.empty(pk.pc_score_workspace_bytes(Hq, Hkv, n_rows, capacity, share_heads),
+                                     dtype=torch.uint8, device=device)
+        self._ws_compact = torch.empty(pk.pc_compact_batch_workspace_bytes(n_layers, Hkv, capacity, share_heads),
+                                       dtype=torch.uint8, device=device)
+
+    def reserve(self, n: int):
+        """Views of the next n free rows of every layer: K, V [L][Hkv][n][D], pos [L][Hsel][n][3]."""
+        if self.nk + n > self.capacity:
+            raise ValueError(f"cache capacity {self.capacity} < {self.nk} + {n}")
+        a = self.nk
+        return self.K[:, :, a:a + n], self.V[:, :, a:a + n], self.pos[:, :, a:a + n]
+
+    def commit(self, n: int, kind: int, frame: int, rotate_with=None) -> None:
+        """Make the n reserved rows part of every layer's cache; rotate_with (int32 [n][3], device)
+        rotates the new keys of all layers in place with one call (layers x KV heads as heads)."""
+        a = self.nk
+        if rotate_with is not None:
+            pk.pc_rope3d(self.K.view(self.L * self.Hkv, self.capacity, self.D)[:, a:a + n], rotate_with,
+                         self.sections, self.base)
+        self.segments.append((a, n, kind, frame))
+        self.nk = a + n
+
+    def budgets(self) -> list[int]:
+        n_past = sum(1 for s in self.segments if s[2] == pk.PC_SEG_FRAME)
+        if self.mode == "pow":
+            per_d = pk.pc_budget(pk.PC_BUDGET_POW, self.n_frame, n_past, self.gamma, self.b_min)
+        else:
+            per_d = pk.pc_budget(MODES[self.mode], self.budget_tokens, n_past, self.gamma, self.b_min)
+        return pk.segment_budgets(self.segments, per_d)
+
+    def _prunable_span(self, budgets):
+        prunable = [s for s, b in zip(self.segments, budgets) if s[2] == pk.PC_SEG_FRAME and b < s[1]]
+        return (prunable[0][0], prunable[-1][0] + prunable[-1][1]) if prunable else None
+
+    def attend(self, layer: int, Q, O=None, lse=None):
+        """Layer `layer`'s (rotated) queries over its cache as it stands -> O (and the log-sum-exp)."""
+        return pk.pc_frame_attn(Q, self.K[layer], self.V[layer], self.nk, self.call_scale, O=O, lse=lse,
+                                ws=self._ws_attn)
+
+    def score_layer(self, layer: int, Q, lse=None) -> None:
+        """Importance of layer `layer`'s cached keys under Q (lse: the log-sum-exp attend() gave for
+        the same queries over the same cache; without it pc_score takes its extra pass)."""
+        span = self._prunable_span(self.budgets())
+        if span is None:
+            return
+        pk.pc_score(Q, self.K[layer], self.nk, self.call_scale, lse=lse, score=self.score[layer],
+                    share_heads=self.share_heads, ws=self._ws_score, q_rows=self.q_rows, key_range=span)
+
+    def repack(self) -> None:
+        """End of the frame step: every layer keeps, per past frame, its top-budget keys; one
+        select launch and one gather launch for the whole stack, in place."""
+        budgets = self.budgets()
+        if self._prunable_span(budgets) is None:
+            return
+        self.segments, self.nk = pk.pc_compact_batch(self.K, self.V, self.pos, self.score, self.segments, budgets,
+                                                     share_heads=self.share_heads, ws=self._ws_compact)

@@ -305,3 +305,36 @@ class DeviceRollingStream:
         """Queries of the step that generates frame `step` (1-based)."""
         rep = self.hq // self.hkv
         self._fill(out_q, float(np.sqrt(self.d)) * self.w[step - 1].repeat_interleave(rep, dim=0))
+
+
+def device_frame_layer(seed: int, n_past: int, K_out, V_out, Q_out, n_text: int = 256, gh: int = 48, gw: int = 84,
+                       sections=(32, 48, 48)) -> None:
+    """The frame_layer recipe drawn on the GPU (seeded torch generator) into caller-provided
+    bf16 buffers: K_out, V_out [Hkv][Nk][D], Q_out [Hq][n][D] or None.  For stacks of layers too
+    large to draw on the host: every layer gets its own seed, hence its own keys, scores and
+    selected rows."""
+    import torch
+    hkv, nk, d = K_out.shape
+    n = gh * gw
+    assert nk == n_text + n * (1 + n_past)
+    dev = K_out.device
+    lf = low_frequency_dims(tuple(sections))
+    rng = np.random.default_rng(seed)
+    u = np.zeros((hkv, d), np.float32)
+    u[:, lf] = rng.standard_normal((hkv, lf.size)).astype(np.float32)
+    u /= np.linalg.norm(u, axis=1, keepdims=True)
+    ud = torch.from_numpy(u).to(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    K_out.normal_(generator=gen)
+    V_out.normal_(generator=gen)
+    bias = torch.empty((hkv, nk, 1), dtype=torch.float32, device=dev)
+    bias[:, : n_text + n] = 0.5
+    for f in range(1, n_past + 1):
+        a = n_text + n * f
+        bias[:, a:a + n] = 0.3 * 0.9 ** (n_past + 1 - f)
+    K_out.add_((bias * ud[:, None, :]).to(K_out.dtype))
+    if Q_out is not None:
+        rep = Q_out.shape[0] // hkv
+        Q_out.normal_(generator=gen)
+        Q_out.add_((float(np.sqrt(d)) * ud.repeat_interleave(rep, dim=0))[:, None, :].to(Q_out.dtype))

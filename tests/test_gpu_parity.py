@@ -227,6 +227,33 @@ def test_frame_attn_bf16_key_shares_and_merge(hq, hkv, nq, nk, fold):
     assert (split.float() - whole.float()).abs().max().item() <= 2 ** -6   # two roundings of values of O(1)
 
 
+@pytest.mark.parametrize("fold", [False, True])
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_frame_attn_bf16_error_bound_at_twice_the_workload_amplitude(seed, fold):
+    """The absolute bar (max 2e-2) presumes outputs of the workloads' size, |O| < 2.  With Q and K
+    at twice the amplitude the softmax is peaked and an output follows single V rows, so |O|
+    reaches 2..4, where bf16 values lie 2^-6 apart.  What the arithmetic guarantees at ANY
+    amplitude: the final rounding of O (at most 2^-8 |O|) plus the rounding of the probabilities
+    to bf16 before the second product (at most 2^-8 sum_j p_j |v_j|; the normaliser is summed
+    from the un-rounded ones) plus fp32 effects.  Checked element by element; for |V| <= 3.5
+    (so |O| < 4) that is at most 0.0078 + 0.0137, which gives the documented max 2.5e-2."""
+    rng = np.random.default_rng(1234 + seed)
+    hq, hkv, nq, nk, d = 4, 2, 333, 2500 - 300 * seed, 128
+    Q = synth.to_bf16((2.0 * rng.standard_normal((hq, nq, d))).astype(np.float32))
+    K = synth.to_bf16((2.0 * rng.standard_normal((hkv, nk, d))).astype(np.float32))
+    V = synth.to_bf16(np.clip(rng.standard_normal((hkv, nk, d)), -3.5, 3.5).astype(np.float32))
+    scale = d ** -0.5
+    if fold:
+        Q, scale = _fold(Q, scale)
+    O = pk.pc_frame_attn(dev(Q, "bf16"), dev(K, "bf16"), dev(V, "bf16"), nk, scale)
+    Ow, _ = orc.frame_attn(Q, K, V, scale)
+    Aw, _ = orc.frame_attn(Q, K, np.abs(V), scale)              # sum_j p_j |v_j|
+    err = np.abs(host(O).astype(np.float64) - Ow)
+    assert np.abs(Ow).max() > 2.0, "the case must reach outputs beyond the workloads' size"
+    assert np.all(err <= 2.0 ** -8 * (np.abs(Ow) + Aw) + 5e-4), (err - 2.0 ** -8 * (np.abs(Ow) + Aw)).max()
+    assert err.max() <= 2.5e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
+
+
 def test_frame_attn_bf16_closed_forms():
     Q, K, V = _attn_case("bf16", 2, 1, 70, 200, 128, 3)
     Ke = np.repeat(K[:, :1], 200, axis=1)                     # all keys equal -> mean of V

@@ -12,7 +12,7 @@ import paper_2601_04359_amd as pk
 from paper_2601_04359_amd import synth
 from paper_2601_04359_amd.rollout import RollingLayer
 
-from test_gpu_parity import DEV, LN2, dev, host, q_fold
+from test_gpu_parity import DEV, LN2, check_selection, dev, host, q_fold
 
 pytestmark = pytest.mark.gpu
 
@@ -226,3 +226,226 @@ def test_sliding_window_with_rebase_matches_oracle_fp32(mode, b_min):
         assert np.abs(host(layer.K[:, :nk]) - w["K"]).max() <= 1e-5
         assert np.array_equal(host(layer.V[:, :nk]).astype(np.float64), w["V"])
         assert np.abs(host(O) - w["O"]).max() <= 2e-5
+
+
+# ---------------------------------------------------------------------------------------------
+# One step of the rolling layer against the oracle applied to the bits the DEVICE holds when the
+# step begins (cache rows after insertion / rebase, rotated queries).  A chain in bf16 cannot be
+# compared end to end bit for bit: the device rotates in fp32 and the oracle in fp64, so now and
+# then a stored element differs by one bf16 step and every later score moves with it.  Taking
+# the device's state as the input of each oracle step checks every transition of the chain at
+# the stated bars; what the device's rotations themselves produce is compared separately, to
+# one rounding of the storage format.
+# ---------------------------------------------------------------------------------------------
+def _snapshot(layer):
+    nk = layer.nk
+    return {"K": host(layer.K[:, :nk]).astype(np.float64), "V": host(layer.V[:, :nk]).astype(np.float64),
+            "pos": host(layer.pos[:, :nk]), "segments": list(layer.segments)}
+
+
+def _source_rows(before, after_pos, plan):
+    """Source row (in the cache before the step) of every packed row, found by its (t, h, w) inside
+    its own segment (coordinates are unique within a segment)."""
+    hsel = after_pos.shape[0]
+    out = np.empty(after_pos.shape[:2], dtype=np.int64)
+    for h in range(hsel):
+        for (start, length, _, _), (ps, pl, _, _) in zip(before["segments"], plan):
+            where = {tuple(p): start + j for j, p in enumerate(before["pos"][h, start:start + length])}
+            assert len(where) == length, "coordinates inside a segment must be unique"
+            for j in range(pl):
+                out[h, ps + j] = where[tuple(after_pos[h, ps + j])]
+    return out
+
+
+def _check_step(before, Qrot, layer, O, budgets_by_distance, scale, score_rows, share, band=1e-6):
+    segs = before["segments"]
+    n_past = sum(1 for s in segs if s[2] == pk.PC_SEG_FRAME)
+    budgets = pk.segment_budgets(segs, budgets_by_distance(n_past))
+    plan = orc.packed_segments(segs, budgets)
+    assert layer.segments == plan
+    nk = layer.nk
+    after_pos = host(layer.pos[:, :nk])
+    idx = _source_rows(before, after_pos, plan)
+    sco = orc.score(Qrot[:, score_rows], before["K"], scale, share_heads=share)
+    n_ex = check_selection(idx, sco, segs, [min(b, s[1]) for b, s in zip(budgets, segs)], band=band)
+    Kd, Vd = host(layer.K[:, :nk]).astype(np.float64), host(layer.V[:, :nk]).astype(np.float64)
+    hkv = Kd.shape[0]
+    for g in range(hkv):                      # rows moved bit for bit
+        src = idx[0 if share else g]
+        assert np.array_equal(Kd[g], before["K"][g][src]) and np.array_equal(Vd[g], before["V"][g][src])
+    Ow, _ = orc.frame_attn(Qrot, Kd, Vd, scale)
+    err = np.abs(host(O).astype(np.float64) - Ow)
+    assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
+    return n_ex
+
+
+@pytest.mark.parametrize("mode,b_min", [("half", 60), ("slide", 0), ("norm", 80)])
+def test_sliding_window_with_rebase_bf16_chain(mode, b_min):
+    """The sliding-window chain at the dtype the benchmark runs it in: keys rotated on insert and
+    rounded to bf16, rebased and rounded again whenever the window advances (Sec. 3.4, the rebase
+    equation), cache re-packed in place every step."""
+    case = synth.rolling_case(seed=21, n_steps=7, hq=4, hkv=2, d=128)
+    n, t_scale, gamma = case.n_frame, 4, 0.7
+    rot = (case.sections, case.base)
+    bfn = _budget_fn(mode, case, gamma, b_min)
+    want = orc.rolling_rollout(case.anchor_K, case.anchor_V, case.anchor_pos, case.anchor_segments, case.frames,
+                               case.queries, case.scale, bfn, score_rows=case.score_rows, rotate=rot,
+                               query_pos=case.query_pos, rebase_t_scale=t_scale, storage=orc.round_to_bf16)
+    assert want[-1]["shift"] > 0, "the case must slide"
+    layer = RollingLayer(case.Hq, case.Hkv, case.D, case.anchor_K.shape[1] + 3 * n, n, case.scale, mode=mode,
+                         gamma=gamma, b_min=b_min, n_score=case.score_rows.size, sections=case.sections,
+                         base=case.base, device=DEV, slide_t_scale=t_scale)
+    k, v, p = layer.reserve(case.anchor_K.shape[1])
+    k.copy_(dev(case.anchor_K, "bf16")); v.copy_(dev(case.anchor_V, "bf16"))
+    apos = dev(case.anchor_pos, None)
+    p.copy_(apos[None].expand_as(p))
+    for (start, length, kind, frame) in case.anchor_segments:
+        layer.commit(length, kind, frame, rotate_with=apos[start:start + length])
+    one_rounding = lambda got, ref: np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-6)
+    same_rows, all_rows = 0, 0
+    for i, Q in enumerate(case.queries):
+        kept = _snapshot(layer)                                  # the cache the previous step left
+        shift_before = layer.shift
+        shift = layer.advance_window()
+        assert shift == want[i]["shift"]                         # host bookkeeping: exact
+        if shift != shift_before:                                # the device's rebase, to one bf16 rounding
+            first = next(j for j, s in enumerate(layer.segments) if s[2] == pk.PC_SEG_FRAME)
+            a = layer.segments[first][0]
+            Kr, pr = orc.rebase(kept["K"][:, a:kept["K"].shape[1]], kept["pos"][:, a:], shift - shift_before, *rot)
+            now = _snapshot(layer)
+            assert now["K"].shape[1] == kept["K"].shape[1]
+            assert one_rounding(now["K"][:, a:], Kr) and np.array_equal(now["pos"][:, a:], pr)
+            assert np.array_equal(now["K"][:, :a], kept["K"][:, :a]) and np.array_equal(now["V"], kept["V"])
+        if i >= 1:
+            Kf, Vf, pf = case.frames[i - 1]
+            pf = pf.copy(); pf[:, 0] -= shift
+            k, v, p = layer.reserve(n)
+            k.copy_(dev(Kf, "bf16")); v.copy_(dev(Vf, "bf16"))
+            pfd = dev(pf, None)
+            p.copy_(pfd[None].expand_as(p))
+            a = layer.nk
+            layer.commit(n, pk.PC_SEG_FRAME, i, rotate_with=pfd)
+            assert one_rounding(host(layer.K[:, a:a + n]).astype(np.float64), orc.rope3d(Kf, pf, *rot))
+        before = _snapshot(layer)
+        qp = case.query_pos[i].copy(); qp[:, 0] -= shift
+        Qd = dev(Q, "bf16")
+        O = layer.step(Qd, q_pos=dev(qp, None))
+        Qrot = host(Qd).astype(np.float64)                       # the rotated queries as the device holds them
+        assert one_rounding(Qrot, orc.rope3d(Q, qp, *rot))
+        _check_step(before, Qrot, layer, O, bfn, case.scale, case.score_rows, False)
+        # the whole chain against the oracle's own chain (fp64 rotations rounded to bf16): tables and
+        # shifts are exact; kept rows agree except where a rotation rounded the other way
+        w = want[i]
+        assert layer.segments == w["segments"] and layer.nk == w["K"].shape[1]
+        got_pos = host(layer.pos[:, :layer.nk])
+        same_rows += int(np.all(got_pos == w["pos"], axis=2).sum())
+        all_rows += got_pos.shape[0] * got_pos.shape[1]
+        err = np.abs(host(O).astype(np.float64) - w["O"])
+        assert err.mean() <= 2e-3, (mode, i, err.mean())
+    assert same_rows >= 0.98 * all_rows, (same_rows, all_rows)
+
+
+@pytest.mark.parametrize("mode,gamma,b_min,share", [("pow", 0.85, 32, False), ("half", 1.0, 40, True)])
+def test_cache_mask_removes_masked_rows_on_insert_and_matches_the_oracle_on_the_deleted_frames(mode, gamma, b_min, share):
+    """Sec. 3.1: a binary mask says which generated tokens enter the cache, and masked entries are
+    ignored in attention; Sec. 3.4: they are removed, not stored.  The rolling layer deletes a new
+    frame's masked rows when the frame is committed, so neither the scoring softmax nor the
+    attention ever sees them: the oracle's rollout on frames with those rows deleted beforehand."""
+    case = synth.rolling_case(seed=13, n_steps=6)
+    aK, frames, queries = _rotated(case)
+    rng = np.random.default_rng(99)
+    masks = [rng.random(case.n_frame) < 0.55 for _ in frames]
+    masks[2][:] = True                                           # one frame enters whole
+    deleted = [(K[:, m], V[:, m], p[m]) for (K, V, p), m in zip(frames, masks)]
+    bfn = _budget_fn(mode, case, gamma, b_min)
+    want = orc.rolling_rollout(aK, case.anchor_V, case.anchor_pos, case.anchor_segments, deleted, queries,
+                               case.scale, bfn, score_rows=case.score_rows, share_heads=share)
+    n = case.n_frame
+    layer = RollingLayer(case.Hq, case.Hkv, case.D, case.anchor_K.shape[1] + len(frames) * n, n, case.scale,
+                         mode=mode, gamma=gamma, b_min=b_min, n_score=case.score_rows.size,
+                         sections=case.sections, base=case.base, device=DEV, share_heads=share)
+    for (start, length, kind, frame) in case.anchor_segments:
+        _insert(layer, aK[:, start:start + length], case.anchor_V[:, start:start + length],
+                case.anchor_pos[start:start + length], kind, frame)
+    for i, Q in enumerate(queries):
+        if i >= 1:
+            Kf, Vf, pf = frames[i - 1]
+            k, v, pp = layer.reserve(n)
+            k.copy_(dev(Kf.astype(np.float32), "bf16")); v.copy_(dev(Vf, "bf16"))
+            pp.copy_(dev(np.broadcast_to(pf[None], (pp.shape[0], n, 3)).copy(), None))
+            a = layer.nk
+            layer.commit(n, pk.PC_SEG_FRAME, i, valid=masks[i - 1].astype(np.uint8))
+            m = int(masks[i - 1].sum())
+            assert layer.nk == a + m and layer.segments[-1] == (a, m, pk.PC_SEG_FRAME, i)
+            # exactly the unmasked rows, in order, bit for bit
+            assert np.array_equal(host(layer.K[:, a:a + m]).astype(np.float64), deleted[i - 1][0])
+            assert np.array_equal(host(layer.pos[0, a:a + m]), deleted[i - 1][2])
+        before = _snapshot(layer)
+        Qd = dev(Q.astype(np.float32), "bf16")
+        O = layer.step(Qd)
+        _check_step(before, Q, layer, O, bfn, case.scale, case.score_rows, share)
+        w = want[i]
+        assert layer.segments == w["segments"], (mode, i)
+        nk = layer.nk
+        assert np.array_equal(host(layer.pos[:, :nk]), w["pos"]), f"step {i + 1}: kept set differs"
+        assert np.array_equal(host(layer.K[:, :nk]).astype(np.float64), w["K"])
+        err = np.abs(host(O).astype(np.float64) - w["O"])
+        assert err.max() <= 2e-2 and err.mean() <= 2e-3, (mode, i, err.max(), err.mean())
+
+
+@pytest.mark.parametrize("mode,gamma,b_min,share,fold", [("pow", 0.85, 32, False, True), ("half", 1.0, 40, True, False)])
+def test_rolling_stack_repacks_all_layers_at_the_step_boundary_like_the_oracle(mode, gamma, b_min, share, fold):
+    """A stack of layers that attends over the cache as it stands, scores from that pass's
+    log-sum-exp and re-packs all layers with ONE batched compaction when the step ends.  Per
+    layer, against the oracle: the attention is exact attention over the un-packed cache of the
+    step, and the cache the re-pack leaves is the oracle rollout's cache of the same step."""
+    from paper_2601_04359_amd.rollout import RollingStack
+    cases = [synth.rolling_case(seed=s, n_steps=5) for s in (11, 12, 13)]
+    c0 = cases[0]
+    n = c0.n_frame
+    rot = [_rotated(c, q_fold(c.scale) if fold else 1.0) for c in cases]
+    scale = LN2 if fold else c0.scale
+    bfn = _budget_fn(mode, c0, gamma, b_min)
+    want = [orc.rolling_rollout(aK, c.anchor_V, c.anchor_pos, c.anchor_segments, frames, queries, scale, bfn,
+                                score_rows=c.score_rows, share_heads=share)
+            for c, (aK, frames, queries) in zip(cases, rot)]
+    stack = RollingStack(len(cases), c0.Hq, c0.Hkv, c0.D, c0.anchor_K.shape[1] + 5 * n, n, c0.scale, mode=mode,
+                         gamma=gamma, b_min=b_min, n_score=c0.score_rows.size, sections=c0.sections, base=c0.base,
+                         device=DEV, share_heads=share, fold_scale=fold)
+
+    def insert(parts, pos_rows, kind, frame):          # parts[l] = (K, V) of layer l
+        m = parts[0][0].shape[1]
+        k, v, p = stack.reserve(m)
+        for l, (Kl, Vl) in enumerate(parts):
+            k[l].copy_(dev(np.asarray(Kl, dtype=np.float32), "bf16"))
+            v[l].copy_(dev(np.asarray(Vl, dtype=np.float32), "bf16"))
+        p.copy_(dev(np.ascontiguousarray(pos_rows), None)[None, None].expand_as(p))
+        stack.commit(m, kind, frame)
+
+    for (start, length, kind, frame) in c0.anchor_segments:
+        insert([(aK[:, start:start + length], c.anchor_V[:, start:start + length]) for c, (aK, _, _) in zip(cases, rot)],
+               c0.anchor_pos[start:start + length], kind, frame)
+    lse = torch.empty((c0.Hq, n), dtype=torch.float32, device=DEV)
+    for i in range(5):
+        if i >= 1:
+            insert([(frames[i - 1][0], frames[i - 1][1]) for (_, frames, _) in rot], rot[0][1][i - 1][2],
+                   pk.PC_SEG_FRAME, i)
+        nk_before = stack.nk
+        pre = [(host(stack.K[l, :, :nk_before]).astype(np.float64), host(stack.V[l, :, :nk_before]).astype(np.float64))
+               for l in range(len(cases))]
+        outs = []
+        for l, (_, _, queries) in enumerate(rot):
+            Qd = dev(queries[i].astype(np.float32), "bf16")
+            outs.append(stack.attend(l, Qd, lse=lse))
+            stack.score_layer(l, Qd, lse=lse)
+        stack.repack()
+        for l, (_, _, queries) in enumerate(rot):
+            Ow, _ = orc.frame_attn(queries[i], pre[l][0], pre[l][1], scale)     # over the un-packed cache
+            err = np.abs(host(outs[l]).astype(np.float64) - Ow)
+            assert err.max() <= 2e-2 and err.mean() <= 2e-3, (l, i, err.max(), err.mean())
+            w = want[l][i]
+            assert stack.segments == w["segments"], (mode, l, i)
+            nk = stack.nk
+            assert np.array_equal(host(stack.pos[l, :, :nk]), w["pos"]), f"layer {l} step {i + 1}: kept set differs"
+            assert np.array_equal(host(stack.K[l, :, :nk]).astype(np.float64), w["K"])
+            assert np.array_equal(host(stack.V[l, :, :nk]).astype(np.float64), w["V"])
