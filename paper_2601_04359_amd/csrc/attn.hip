@@ -104,6 +104,9 @@ __device__ __forceinline__ void pipeline_phase(
   f32x16 s_acc = zero;
   float psum = 0.f;
   float pv[16];
+  // The wave asks for issue priority over its SIMD neighbour while it is inside the interleaved
+  // matrix / vector block, and gives it back for the bookkeeping behind it (measured: +0.5 %).
+  __builtin_amdgcn_s_setprio(1);
 #pragma unroll
   for (int k = 0; k < 16; ++k) {
     const bf16x8 f = ring[k % kRing];
@@ -122,6 +125,7 @@ __device__ __forceinline__ void pipeline_phase(
     }
     __builtin_amdgcn_sched_barrier(0);
   }
+  __builtin_amdgcn_s_setprio(0);
   // keep the vector results in this basic block (otherwise they sink below the next branch)
 #pragma unroll
   for (int half = 0; half < 2; ++half) asm volatile("" : "+v"(p_cur[half]));
