@@ -220,6 +220,32 @@ int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,
                void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * pc_compact_static -- pc_compact for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, results and errors as pc_compact, minus ws / ws_bytes: the
+ * scratch (kept-row indices, tickets and flags of the in-place gather) lives in an array of
+ * PC_COMPACT_STATIC_BYTES that is part of the library's device image; every GPU the library
+ * runs on holds it until the process ends.  The call allocates and frees nothing.
+ *   - A request that needs more than the array holds (pc_compact_workspace_bytes(Hkv, Nk_in,
+ *     share_heads) > pc_compact_static_capacity()) is rejected with PC_ERR_WORKSPACE before any
+ *     device work; use pc_compact with a workspace of your own for it.  The array covers
+ *     4 KV heads x 193,792 rows (the 48-frame cache) and 8 KV heads x 98,304 rows.
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's contents; every
+ *     call clears what it needs with its own kernel first.  Calls that overlap on one GPU (two
+ *     streams, two host threads) race on it: issue them one after another on one stream, or
+ *     order them with events.
+ */
+#define PC_COMPACT_STATIC_BYTES (4u << 20)
+size_t pc_compact_static_capacity(void);
+int pc_compact_static(void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,
+                      int64_t kv_stride_h, int64_t pos_stride_h, const float* score,
+                      int64_t score_stride_h, const pc_segment* seg_in, int n_seg,
+                      const int32_t* budget, int share_heads, void* K_out, void* V_out,
+                      int32_t* pos_out, int64_t kv_out_stride_h, int64_t pos_out_stride_h,
+                      int32_t* idx_out, int64_t idx_stride_h, pc_segment* seg_out, int32_t* Nk_out,
+                      void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * pc_compact_batch -- pc_compact for n_layers layers at once (the caches of a layer stack are
  * re-packed together at a frame-step boundary): one select launch and one gather launch
  * cover every layer, so the small per-layer launches neither queue behind each other nor

@@ -14,7 +14,7 @@ __all__ = [
     "PC_BUDGET_POW", "PC_BUDGET_NORM", "PC_BUDGET_HALF", "PC_BUDGET_SLIDE", "PC_MAX_SEGMENTS",
     "PackCacheError", "lib", "lib_path", "pc_version", "pc_strerror", "pc_budget", "pc_rope3d", "pc_rebase",
     "pc_score", "pc_score_workspace_bytes", "pc_compact_plan", "pc_compact", "pc_compact_batch", "pc_compact_batch_workspace_bytes", "PC_COMPACT_SELECT", "PC_COMPACT_GATHER", "PC_SCALE_FOLDED", "folded_q_scale", "pc_masked_budgets", "pc_mask_scores", "pc_compact_status",
-    "pc_compact_workspace_bytes", "pc_compact_prepared", "pc_frame_attn", "pc_frame_attn_workspace_bytes",
+    "pc_compact_workspace_bytes", "pc_compact_prepared", "pc_compact_static", "pc_compact_static_capacity", "pc_frame_attn", "pc_frame_attn_workspace_bytes",
     "segment_budgets",
 ]
 
@@ -88,6 +88,9 @@ def lib() -> C.CDLL:
         L.pc_compact_workspace_bytes.argtypes = [C.c_int] * 3
         L.pc_compact.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, i64, i64, vp, i64, segp, C.c_int,
                                  i32p, C.c_int, vp, vp, vp, i64, i64, vp, i64, segp, i32p, vp, sz, vp]
+        L.pc_compact_static_capacity.restype = sz
+        L.pc_compact_static_capacity.argtypes = []
+        L.pc_compact_static.argtypes = L.pc_compact.argtypes[:-3] + [vp]
         L.pc_frame_attn_workspace_bytes.restype = sz
         L.pc_frame_attn_workspace_bytes.argtypes = [C.c_int] * 4
         L.pc_frame_attn.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, i64,
@@ -290,6 +293,29 @@ def pc_compact(K, V, pos, score, segments, budgets, share_heads: bool = False, o
                             Ko.data_ptr(), Vo.data_ptr(), po.data_ptr(), Ko.stride(0), po.stride(0),
                             _ptr(idx), 0 if idx is None else idx.stride(0), seg_out, C.byref(nk),
                             ws.data_ptr(), ws.numel(), _stream()))
+    return [(s.start, s.len, s.kind, s.frame) for s in seg_out[:n]], nk.value
+
+
+def pc_compact_static_capacity() -> int:
+    return lib().pc_compact_static_capacity()
+
+
+def pc_compact_static(K, V, pos, score, segments, budgets, share_heads: bool = False, out=None, idx=None):
+    """pc_compact without a workspace argument: the scratch is an array inside the library (at
+    most pc_compact_static_capacity() bytes; larger requests raise).  Nothing is allocated, here
+    or in the library.  Calls that overlap on one GPU race on that array."""
+    Hkv, _, D = K.shape
+    _check_kv_layout(K, V, pos, out, share_heads)
+    n = len(segments)
+    seg_in = _seg_array(segments)
+    seg_out = (pc_segment * max(n, 1))()
+    b = (C.c_int32 * max(n, 1))(*[int(v) for v in budgets])
+    nk = C.c_int32(0)
+    Ko, Vo, po = (K, V, pos) if out is None else out
+    _check(lib().pc_compact_static(K.data_ptr(), V.data_ptr(), pos.data_ptr(), _dtype_code(K), Hkv, D, K.stride(0),
+                                   pos.stride(0), score.data_ptr(), score.stride(0), seg_in, n, b, int(share_heads),
+                                   Ko.data_ptr(), Vo.data_ptr(), po.data_ptr(), Ko.stride(0), po.stride(0),
+                                   _ptr(idx), 0 if idx is None else idx.stride(0), seg_out, C.byref(nk), _stream()))
     return [(s.start, s.len, s.kind, s.frame) for s in seg_out[:n]], nk.value
 
 

@@ -495,6 +495,35 @@ WsLayout ws_layout(int n_layers, int Hkv, int Nk_in, int share_heads) {
   return w;
 }
 
+// ---- pc_compact_static: the workspace as a file-scope device array ---------------------------
+// For callers that cannot allocate.  Every GPU the library runs on holds its own copy of the
+// array at its own address; in host code the array's NAME is only a handle for
+// hipGetSymbolAddress, never a device address: kernels and every other use get the pointer
+// looked up once per device.
+static __device__ __align__(256) unsigned char scratch[PC_COMPACT_STATIC_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // per device: where its copy of `scratch` lives
+
+// Device address of the current device's copy of the array (looked up on the first call on that
+// device, with that device current).  Safe from several host threads: they all get the same answer.
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  PC_REQUIRE(e == hipSuccess, PC_ERR_HIP, "pc_compact_static: hipGetDevice: %s", hipGetErrorString(e));
+  PC_REQUIRE(dev >= 0 && dev < kMaxDevices, PC_ERR_UNSUPPORTED, "pc_compact_static: device %d outside [0, %d)", dev,
+             kMaxDevices);
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    PC_REQUIRE(e == hipSuccess && p != nullptr, PC_ERR_HIP, "pc_compact_static: hipGetSymbolAddress: %s",
+               hipGetErrorString(e));
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return PC_OK;
+}
+
 }  // namespace
 }  // namespace pc
 
@@ -520,6 +549,34 @@ extern "C" int pc_compact(void* K, void* V, int32_t* pos, int dtype, int Hkv, in
   return pc_compact_batch(1, K, V, pos, dtype, Hkv, D, kv_stride_h, 0, pos_stride_h, 0, score, score_stride_h, 0,
                           seg_in, n_seg, budget, share_heads, K_out, V_out, pos_out, kv_out_stride_h, 0,
                           pos_out_stride_h, 0, idx_out, idx_stride_h, 0, seg_out, Nk_out, ws, ws_bytes, stream);
+}
+
+extern "C" size_t pc_compact_static_capacity(void) { return PC_COMPACT_STATIC_BYTES; }
+
+extern "C" int pc_compact_static(void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,
+                                 int64_t kv_stride_h, int64_t pos_stride_h, const float* score,
+                                 int64_t score_stride_h, const pc_segment* seg_in, int n_seg,
+                                 const int32_t* budget, int share_heads, void* K_out, void* V_out,
+                                 int32_t* pos_out, int64_t kv_out_stride_h, int64_t pos_out_stride_h,
+                                 int32_t* idx_out, int64_t idx_stride_h, pc_segment* seg_out,
+                                 int32_t* Nk_out, void* stream) {
+  PC_REQUIRE(Hkv > 0 && n_seg >= 0 && n_seg <= PC_MAX_SEGMENTS && (n_seg == 0 || seg_in != nullptr), PC_ERR_SHAPE,
+             "pc_compact_static: Hkv=%d n_seg=%d", Hkv, n_seg);
+  const int64_t nk_in = n_seg ? static_cast<int64_t>(seg_in[n_seg - 1].start) + seg_in[n_seg - 1].len : 0;
+  PC_REQUIRE(nk_in >= 0 && nk_in <= INT_MAX, PC_ERR_SHAPE, "pc_compact_static: segment table ends at row %lld",
+             static_cast<long long>(nk_in));
+  const size_t need = nk_in ? ws_layout(1, Hkv, static_cast<int>(nk_in), share_heads).total : 0;
+  PC_REQUIRE(need <= PC_COMPACT_STATIC_BYTES, PC_ERR_WORKSPACE,
+             "pc_compact_static: Hkv=%d x %lld rows needs %zu bytes of scratch, the built-in array holds %zu; "
+             "use pc_compact with a workspace of the caller's",
+             Hkv, static_cast<long long>(nk_in), need, static_cast<size_t>(PC_COMPACT_STATIC_BYTES));
+  void* ptr = nullptr;
+  if (int rc = static_scratch(&ptr)) return rc;
+  // the select kernel of every call clears the tickets, flags and abort word it is about to use
+  // (a fill kernel, not a memset), so what the last call left in the array does not matter
+  return pc_compact(K, V, pos, dtype, Hkv, D, kv_stride_h, pos_stride_h, score, score_stride_h, seg_in, n_seg,
+                    budget, share_heads, K_out, V_out, pos_out, kv_out_stride_h, pos_out_stride_h, idx_out,
+                    idx_stride_h, seg_out, Nk_out, ptr, PC_COMPACT_STATIC_BYTES, stream);
 }
 
 extern "C" int pc_compact_batch(int n_layers, void* K, void* V, int32_t* pos, int dtype, int Hkv, int D,

@@ -208,6 +208,23 @@ def test_batched_compaction_and_mask_argument_checks(L):
     assert L.pc_strerror(-8) not in (None, L.pc_strerror(-7))
 
 
+def test_static_scratch_entry_rejects_oversized_requests_before_any_device_work(L):
+    # pc_compact_static: the request is sized on the host and refused before the device is touched
+    assert L.pc_compact_static_capacity() == 4 << 20
+    assert L.pc_compact_workspace_bytes(4, 193_792, 0) <= L.pc_compact_static_capacity()
+    one = C.c_void_p(4096)
+    n = 400_000
+    assert L.pc_compact_workspace_bytes(8, n, 0) > L.pc_compact_static_capacity()
+    seg = (binding.pc_segment * 1)(binding.pc_segment(0, n, 1, 0))
+    bud = (C.c_int32 * 1)(n)
+    rc = L.pc_compact_static(one, one, one, 1, 8, 128, n * 128, n * 3, one, n, seg, 1, bud, 0, one, one, one,
+                             n * 128, n * 3, None, 0, None, None, None)
+    assert rc == -6 and b"scratch" in L.pc_last_error_detail()
+    # malformed table: refused as a shape error, also before any device work
+    assert L.pc_compact_static(one, one, one, 1, 0, 128, 0, 0, one, 0, seg, 1, bud, 0, one, one, one, 0, 0, None,
+                               0, None, None, None) == -2
+
+
 def test_fold_helpers_are_the_constants_the_header_names():
     import math
     assert pk.PC_SCALE_FOLDED == math.log(2.0)
