@@ -65,19 +65,19 @@ __device__ __forceinline__ void stage_rows(Src&& src, uint32_t lds_tile, int wav
 // acc[b] = init(b) + (32 streamed rows at `half`) x (stationary block b)^T, 16 products; after
 // each product epi(i) runs one sixteenth of the vector work of the previous half tile.
 // kInit = false: the products start from zero and init is not called.
+// ring holds the first four fragments of `half` on entry (fetched while the phase before ran) and
+// the first four of `next_half` on exit, so that no phase starts by waiting for LDS.
 template <bool kInit, class Init, class Epi>
-__device__ __forceinline__ void stream_phase(const lds_u8* half, const int (&a_off)[8],
-                                             const bf16x8 (&st)[2][8], f32x16 (&acc)[2], Init&& init, Epi&& epi) {
-  bf16x8 ring[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) ring[r] = lds_frag(half + a_off[r]);
+__device__ __forceinline__ void stream_phase(const lds_u8* half, const lds_u8* next_half, const int (&a_off)[8],
+                                             const bf16x8 (&st)[2][8], f32x16 (&acc)[2], Init&& init, Epi&& epi,
+                                             bf16x8 (&ring)[4]) {
   f32x16 zero;
 #pragma unroll
   for (int i = 0; i < 16; ++i) zero[i] = 0.f;
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
     const bf16x8 a = ring[s & 3];
-    if (s + 4 < 8) ring[s & 3] = lds_frag(half + a_off[s + 4]);
+    ring[s & 3] = s + 4 < 8 ? lds_frag(half + a_off[s + 4]) : lds_frag(next_half + a_off[s - 4]);
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       if constexpr (kInit)
@@ -209,7 +209,10 @@ __global__ __launch_bounds__(kThreads, 1) void score_rowpass_bf16(
   stage(2);
   asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
   __syncthreads();
-  stream_phase<false>(slot(0), a_off, qf, sA, NoInit{}, [](int) {});
+  bf16x8 ring[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) ring[r] = lds_frag(slot(0) + a_off[r]);
+  stream_phase<false>(slot(0), slot(0) + 32 * kRowBytes, a_off, qf, sA, NoInit{}, [](int) {}, ring);
   // Tile j lives in LDS slot j % 4; the loop is unrolled over the slots so that their bases are
   // immediates of the LDS reads.
   auto tile_body = [&](int j, auto slot_tag) {
@@ -219,13 +222,13 @@ __global__ __launch_bounds__(kThreads, 1) void score_rowpass_bf16(
     __syncthreads();  // tile j+1 has landed everywhere; slot of tile j-1 is free
     stage(j + 3);
     if (tail) mask_keys(sA, (t_begin + j) * kTileRows, Nk, g);
-    stream_phase<false>(smem + u * kTileBytes + 32 * kRowBytes, a_off, qf, sB, NoInit{},
-                        [&](int i) { row_epilogue(i, sA, st, psum, c); });
+    stream_phase<false>(smem + u * kTileBytes + 32 * kRowBytes, smem + ((u + 1) & 3) * kTileBytes, a_off, qf, sB, NoInit{},
+                        [&](int i) { row_epilogue(i, sA, st, psum, c); }, ring);
     row_commit(sA, st, psum, c);
     if (tail) mask_keys(sB, (t_begin + j) * kTileRows + 32, Nk, g);
     if (j + 1 < n) {
-      stream_phase<false>(smem + ((u + 1) & 3) * kTileBytes, a_off, qf, sA, NoInit{},
-                          [&](int i) { row_epilogue(i, sB, st, psum, c); });
+      stream_phase<false>(smem + ((u + 1) & 3) * kTileBytes, smem + ((u + 1) & 3) * kTileBytes + 32 * kRowBytes, a_off, qf,
+                          sA, NoInit{}, [&](int i) { row_epilogue(i, sB, st, psum, c); }, ring);
     } else {
 #pragma unroll
       for (int i = 0; i < 16; ++i) row_epilogue(i, sB, st, psum, c);
@@ -405,7 +408,10 @@ __global__ __launch_bounds__(kThreads, 1) void score_colpass_bf16(
       load_lq(0, 0, initA);
       load_lq(0, 1, initB);
     }
-    stream_phase<kUnitC>(slot(0), a_off, kf, sA, startA, [](int) {});
+    bf16x8 ring[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) ring[r] = lds_frag(slot(0) + a_off[r]);
+    stream_phase<kUnitC>(slot(0), slot(0) + 32 * kRowBytes, a_off, kf, sA, startA, [](int) {}, ring);
     auto tile_body = [&](int j, auto slot_tag) {  // slot j % 4 as a compile-time constant, as in pass 1
       constexpr int u = decltype(slot_tag)::value;
       dma_wait_all_but_newest();
@@ -413,12 +419,12 @@ __global__ __launch_bounds__(kThreads, 1) void score_colpass_bf16(
       stage(j + 3, rows);
       src_rows(j + 4, rows);
       if constexpr (kUnitC) load_lq((u + 1) & 3, 0, initA); else load_lq(u, 0, lq);
-      stream_phase<kUnitC>(smem + u * kTileBytes + 32 * kRowBytes, a_off, kf, sB, startB,
-                           [&](int i) { col_epilogue<kUnitC>(i, sA, lq, colsum, c); });
+      stream_phase<kUnitC>(smem + u * kTileBytes + 32 * kRowBytes, smem + ((u + 1) & 3) * kTileBytes, a_off, kf, sB, startB,
+                           [&](int i) { col_epilogue<kUnitC>(i, sA, lq, colsum, c); }, ring);
       if constexpr (kUnitC) load_lq((u + 1) & 3, 1, initB); else load_lq(u, 1, lq);
       if (j + 1 < n) {
-        stream_phase<kUnitC>(smem + ((u + 1) & 3) * kTileBytes, a_off, kf, sA, startA,
-                             [&](int i) { col_epilogue<kUnitC>(i, sB, lq, colsum, c); });
+        stream_phase<kUnitC>(smem + ((u + 1) & 3) * kTileBytes, smem + ((u + 1) & 3) * kTileBytes + 32 * kRowBytes, a_off, kf,
+                             sA, startA, [&](int i) { col_epilogue<kUnitC>(i, sB, lq, colsum, c); }, ring);
       } else {
 #pragma unroll
         for (int i = 0; i < 16; ++i) col_epilogue<kUnitC>(i, sB, lq, colsum, c);
