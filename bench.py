@@ -85,7 +85,7 @@ def main() -> int:
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-f48", action="store_true", help="skip the frame-48 compaction / dense legs")
     ap.add_argument("--f48-only", default="",
-                    help="frame-48 compaction: run only this variant (layer | batch | graph | streams | copy), "
+                    help="frame-48 compaction: run only this variant (layer | batch | graph | streams | streams7 | copy), "
                          "optionally :gamma (e.g. layer:0.85), so that a kernel trace of the command holds the "
                          "launches of one variant only")
     ap.add_argument("--no-fold", action="store_true",
@@ -319,7 +319,8 @@ def main() -> int:
             return {"ms_per_layer": round(ms, 4), "GBps": round(gb / (ms * 1e-3), 1),
                     "frac_hbm": round(gb / (ms * 1e-3) / PEAK_HBM_GBS, 4)}
 
-        comp, comp_b, comp_p, comp_g, comp_c = {}, {}, {}, {}, {}
+        comp, comp_b, comp_p, comp_g, comp_c, comp_4 = {}, {}, {}, {}, {}, {}
+        lane_streams = [torch.cuda.Stream() for _ in range(7)]
         side_stream = torch.cuda.Stream()
         graph_stream = torch.cuda.Stream()
         ev_sel = [torch.cuda.Event() for _ in range(n_layers)]
@@ -350,6 +351,23 @@ def main() -> int:
                         main.wait_event(ev_sel[l])
                         gat[l]()
                 comp_p[str(gamma)] = entry(timed_stack(two_streams, start=lambda a: side.wait_event(a)), gb)
+            if only in ("", "streams7"):
+                # one pc_compact call per layer again, the layers dealt round-robin over seven streams
+                # (layer caches are independent): the launches of neighbouring layers overlap.  Measured:
+                # 4 streams 0.47 / 0.53 / 0.62 of peak, 7 streams 0.53 / 0.56 / 0.61, 14 streams 0.50 / 0.54 / 0.60
+                # (the process has 4 hardware queues)
+                main = torch.cuda.current_stream()
+                calls4 = [pk.pc_compact_prepared(Kl, Vl, pl, sl, w48.segments, b48, wl, stream=lane_streams[i % len(lane_streams)])
+                          for i, (Kl, Vl, pl, sl, wl) in enumerate(layers)]
+
+                def layer_streams():
+                    for c in calls4:
+                        c()
+                    for st in lane_streams:
+                        lane_done = torch.cuda.Event()
+                        lane_done.record(st)
+                        main.wait_event(lane_done)
+                comp_4[str(gamma)] = entry(timed_stack(layer_streams, start=lambda a: [st.wait_event(a) for st in lane_streams]), gb)
             if only in ("", "batch"):      # the whole stack in one call
                 msb = timed_stack(lambda: pk.pc_compact_batch(KL, VL, PL, SL, w48.segments, b48, ws=ws_b48))
                 comp_b[str(gamma)] = entry(msb, gb)
@@ -383,6 +401,8 @@ def main() -> int:
             out["compaction_f48_in_place_batched"] = comp_b
         if comp_p:
             out["compaction_f48_in_place_two_streams"] = comp_p
+        if comp_4:
+            out["compaction_f48_in_place_layers_over_7_streams"] = comp_4
         if comp_g:
             out["compaction_f48_in_place_graph_replay"] = comp_g
         if comp_c:
