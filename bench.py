@@ -81,7 +81,7 @@ def main() -> int:
     ap.add_argument("--no-rollout-stack", action="store_true",
                     help="skip the second packed rollout, in which every layer attends first, scores from that "
                          "pass's log-sum-exp, and the whole stack is re-packed by ONE batched compaction per step")
-    ap.add_argument("--out-dir", default=os.path.join(ROOT, "gpurun_out"), help="where the per-frame tables go")
+    ap.add_argument("--out-dir", default=os.path.join(ROOT, "bench_out"), help="where the per-frame tables go")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-f48", action="store_true", help="skip the frame-48 compaction / dense legs")
     ap.add_argument("--f48-only", default="",
