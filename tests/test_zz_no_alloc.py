@@ -81,3 +81,32 @@ def test_static_scratch_entry_rejects_what_does_not_fit():
     with pytest.raises(pk.PackCacheError) as e:
         pk.pc_compact_static(t, t, p, s, segs, [n])
     assert e.value.status == -6 and "scratch" in str(e.value)
+
+
+def test_static_scratch_entry_replays_from_a_hip_graph():
+    """What the entry point is for: a caller under graph capture.  After one eager call (which
+    looks the array's address up) the call is recorded and re-played; every replay must give the
+    eager result (the bookkeeping in the array is cleared by a kernel of the call itself)."""
+    w, budgets, mk = _case(43, 7)
+    nk_out = pk.pc_compact_plan(w.segments, budgets)[1]
+    K0, V0, p0, sc = mk()
+    K, V, p = K0.clone(), V0.clone(), p0.clone()
+    idx = torch.empty((w.Hkv, nk_out), dtype=torch.int32, device=DEV)
+
+    def step():
+        K.copy_(K0), V.copy_(V0), p.copy_(p0)
+        pk.pc_compact_static(K, V, p, sc, w.segments, budgets, idx=idx)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (K[:, :nk_out], V[:, :nk_out], p[:, :nk_out], idx)]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for replay in range(3):
+        K.zero_(), idx.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (g, x) in enumerate(zip((K[:, :nk_out], V[:, :nk_out], p[:, :nk_out], idx), want)):
+            assert torch.equal(g, x), f"replay {replay}: output {i} differs from the eager run"
