@@ -310,6 +310,12 @@ int pc_compact_status(const void* ws, void* stream);
  * pc_compact with the masked scores and budgets then keeps, per past frame, the
  * top-budget unmasked tokens and physically removes the rest.  Anchors are not pruned and
  * ignore the mask.
+ * Masked entries are ignored in attention (Sec. 3.1, after Eq. 1): a masked key must not count
+ * in the softmax of pc_score or pc_frame_attn either, and neither call takes a mask.  Remove the
+ * masked rows of a frame when it ENTERS the cache instead: give its rows the score 0, call
+ * pc_mask_scores on them, and call pc_compact over the whole table with the new segment's budget
+ * = its unmasked count and every other segment's budget = its length (rows that stay where they
+ * are cost nothing in place).  Only unmasked rows are then ever scored or attended to.
  * Errors: PC_ERR_NULL, PC_ERR_SHAPE, PC_ERR_BUDGET, PC_ERR_HIP.
  */
 int pc_masked_budgets(const pc_segment* seg, int n_seg, const int32_t* budget, const uint8_t* valid,
