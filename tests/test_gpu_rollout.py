@@ -356,6 +356,7 @@ def test_cache_mask_removes_masked_rows_on_insert_and_matches_the_oracle_on_the_
     rng = np.random.default_rng(99)
     masks = [rng.random(case.n_frame) < 0.55 for _ in frames]
     masks[2][:] = True                                           # one frame enters whole
+    masks[3][:] = False                                          # and one not at all
     deleted = [(K[:, m], V[:, m], p[m]) for (K, V, p), m in zip(frames, masks)]
     bfn = _budget_fn(mode, case, gamma, b_min)
     want = orc.rolling_rollout(aK, case.anchor_V, case.anchor_pos, case.anchor_segments, deleted, queries,
