@@ -74,6 +74,8 @@ __device__ __forceinline__ void stream_phase(const lds_u8* half, const lds_u8* n
   f32x16 zero;
 #pragma unroll
   for (int i = 0; i < 16; ++i) zero[i] = 0.f;
+  // issue priority over the SIMD neighbour while inside the interleaved block (measured: +2-3 %)
+  __builtin_amdgcn_s_setprio(1);
 #pragma unroll
   for (int s = 0; s < 8; ++s) {
     const bf16x8 a = ring[s & 3];
@@ -88,6 +90,7 @@ __device__ __forceinline__ void stream_phase(const lds_u8* half, const lds_u8* n
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  __builtin_amdgcn_s_setprio(0);
 }
 
 // ---- pass 1: per-query (max, sum) over a slice of the keys ---------------------------------
