@@ -6,7 +6,10 @@
 //            and the search stops as soon as the k-th key is alone in its bin); equal scores
 //            are taken lowest index first; the kept indices come out ascending.  Segments
 //            longer than PC_MAX_SELECT_LEN take a one-wave, bit-by-bit variant that re-reads
-//            the scores.
+//            the scores.  A call with many segments (a stack of layers) uses one WAVE per
+//            segment instead: fewer instructions per key and no work-group barriers
+//            (5,488 segments: 56 us -> 34 us; one layer's 196 segments: 10 us -> 15 us, hence
+//            the switch-over at 1,536 segments).
 //   gather   HBM-bound.  A work-group owns 64 consecutive packed rows of one
 //            KV head: it loads its K, V and position rows (16 bytes per lane), then stores
 //            them.  In place, a work-group may only store once every work-group whose SOURCE
@@ -314,6 +317,232 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
     if (kept && at < k) out[at] = start + e0 + i;
     at += kept ? 1 : 0;
     eq_run += is_eq ? 1 : 0;
+  }
+}
+
+// One WAVE per segment (a work-group is one wave), no work-group barrier anywhere: the form for
+// a stack of layers, where thousands of segments fill the chip and the cost is instructions per
+// key, not the latency of one segment.  Lane l keeps keys l, l + 64, l + 128, ... in registers: the
+// n_full = len / 64 rows of 64 keys in key[], the ragged last row (len % 64 keys) in a register of
+// its own.  A sweep over the keys runs from row n_full - 1 down to row 0 behind one scalar
+// compare per row, so a full row costs no per-lane validity test.
+//   * Shared leading bits are skipped as in the block form; then ONE 2,048-bin histogram pass
+//     over the next eleven bits (the wave's own 8 KB of LDS; every key votes, no test).  A lane
+//     sums the 32 bins it owns, a suffix scan over the lanes finds the owner of the k-th key and
+//     32 lanes scan its bins.
+//   * The chosen bin nearly always holds a handful of keys: up to 64 candidates are written to
+//     LDS (ballot + lane count, no atomics), one per lane, and each lane counts the candidates
+//     above / not below its own by reading the others lane by lane; the lane whose counts bracket
+//     the remaining rank holds the threshold.  More than 64 candidates: another histogram pass.
+//   * Output: exactly k keys are kept, so with the rows taken last to first a kept key's position
+//     is k - (kept in later rows) - (kept in this row at its lane or above), a ballot and a lane
+//     count; stores of a row land next to each other.  Equal keys are taken lowest index first.
+#ifndef PC_ROWS_SELECT_MIN_UNITS
+#define PC_ROWS_SELECT_MIN_UNITS 1536
+#endif
+#ifndef PC_ROWS_SELECT_MIN_LEN
+#define PC_ROWS_SELECT_MIN_LEN 1024
+#endif
+// the wave form is used from this many segments per call on (measured cross-over: 7-8 layers of 196
+// segments), when the longest pruned segment is longer than kRowsSelectMinLen
+constexpr int kRowsSelectMinUnits = PC_ROWS_SELECT_MIN_UNITS, kRowsSelectMinLen = PC_ROWS_SELECT_MIN_LEN;
+// f(n - 1), ..., f(0) with compile-time row numbers; n in [0, 64] is wave-uniform
+template <class F>
+__device__ __forceinline__ void rows_down_from(int n, F&& f) {
+#pragma unroll
+  for (int i = 63; i >= 0; --i) {
+    asm volatile("" : "+s"(n));  // one scalar compare here, not 64 lane masks kept from sweep to sweep
+    if (i < n) f(i);
+  }
+}
+
+__device__ __forceinline__ int lanes_below(uint64_t mask, int base) {  // base + set bits of mask below this lane
+  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                   __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), base));
+}
+
+__global__ __launch_bounds__(64) void select_rows_kernel(
+    const float* __restrict__ score, int64_t score_stride_h, int32_t* __restrict__ idx, int64_t idx_stride_h,
+    SegTable tab, int32_t* __restrict__ clear, int n_clear, int hsel, int64_t score_stride_l, int64_t idx_stride_l) {
+  constexpr int kRows = PC_MAX_SELECT_LEN / 64;                     // 64 full rows at most
+  constexpr int kBits = 11, kBins = 1 << kBits, kOwn = kBins / 64;  // 32 bins per lane
+  static_assert(kRows == 64, "rows_down_from covers 64 rows");
+  __shared__ __align__(16) int hist[kBins];
+  const int lane = threadIdx.x;
+  const int s = blockIdx.x, h = blockIdx.y;  // wave-uniform, like everything read from the table
+  for (int i = (h * gridDim.x + s) * 64 + lane; i < n_clear; i += gridDim.x * gridDim.y * 64) clear[i] = 0;
+  const int layer = __builtin_amdgcn_readfirstlane(h / hsel), head = __builtin_amdgcn_readfirstlane(h % hsel);
+  const int start = tab.start[s], len = tab.len[s], k = tab.keep[s];
+  int32_t* out = idx + layer * idx_stride_l + head * idx_stride_h + tab.dst[s];
+  if (k <= 0) return;
+  if (!tab.prune[s]) {
+    for (int e = lane; e < len; e += 64) out[e] = start + e;
+    return;
+  }
+  const float* sc = score + layer * score_stride_l + head * score_stride_h + start;
+  uint32_t* cand = reinterpret_cast<uint32_t*>(hist);  // the candidates reuse the histogram's first words
+  auto wave_sync = [] {  // LDS written by other lanes of this wave becomes visible; nothing moves across
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  const int n_full = len >> 6, tail = len & 63;
+  const bool in_tail = lane < tail;  // this lane has a key in the ragged row
+  uint32_t key[kRows], key_r;
+  {  // every load in flight before the first use; rows past n_full are neither loaded nor looked at
+    float v[kRows];
+    const float v_r = sc[min(n_full * 64 + lane, len - 1)];
+    // a buffer descriptor over the segment's scores (raw 32-bit data; reads past `len` return 0): the
+    // row offset is a scalar operand of the load and the lane's byte offset one register for all
+    // rows, so a load costs no vector address arithmetic
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(sc), 0, len * 4, 0x00020000);
+    const int lane_bytes = lane * 4;
+    rows_down_from(n_full, [&](int i) {
+      v[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, lane_bytes, i * 256, 0));
+    });
+    rows_down_from(n_full, [&](int i) {
+      asm volatile("" : "+v"(v[i]));  // the conversion stays in this sweep, behind all the loads
+      key[i] = order_key(v[i]);
+    });
+    key_r = order_key(v_r);
+  }
+  // bits in which any two keys differ: every key against the segment's first one (one three-input
+  // bit operation per key), then an OR over the lanes
+  const uint32_t key0 = __builtin_amdgcn_readfirstlane(n_full > 0 ? key[0] : key_r);
+  uint32_t differ = in_tail ? key_r ^ key0 : 0u;
+  rows_down_from(n_full, [&](int i) { differ |= key[i] ^ key0; });
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) differ |= __shfl_xor(differ, d, 64);
+  differ = __builtin_amdgcn_readfirstlane(differ);  // the same in every lane: scalar from here on
+  int hi = differ ? 32 - __clz(differ) : 0;  // number of undecided low bits
+  uint32_t prefix = hi >= 32 ? 0u : (key0 >> hi) << hi;
+  int remaining = k;   // rank of the threshold among the keys that match the prefix
+  int eq_total = len;  // keys equal to the threshold once hi == 0
+  bool first = true;
+  while (hi > 0) {
+    const int width = min(kBits, hi), shift = hi - width;
+    int4* h4 = reinterpret_cast<int4*>(hist);
+#pragma unroll
+    for (int j = 0; j < kOwn / 4; ++j) h4[j * 64 + lane] = make_int4(0, 0, 0, 0);
+    wave_sync();
+    // byte offset of a key's bin: the digit times four, as one shift and one mask
+    const uint32_t byte_mask = ((1u << width) - 1u) << 2;
+    const uint32_t rot = static_cast<uint32_t>(shift - 2) & 31u;  // rotate right: bit `shift` lands on bit 2
+    auto vote = [&](uint32_t kv) {
+      const uint32_t off = __builtin_amdgcn_alignbit(kv, kv, rot) & byte_mask;
+      atomicAdd(reinterpret_cast<int*>(reinterpret_cast<char*>(hist) + off), 1);
+    };
+    if (first) {  // every key matches the shared prefix
+      if (in_tail) vote(key_r);
+      rows_down_from(n_full, [&](int i) { vote(key[i]); });
+    } else {
+      const uint32_t hi_mask = 0xFFFFFFFFu << hi;  // hi < 32 after the first pass
+      if (in_tail && (key_r & hi_mask) == prefix) vote(key_r);
+      rows_down_from(n_full, [&](int i) {
+        if ((key[i] & hi_mask) == prefix) vote(key[i]);
+      });
+    }
+    first = false;
+    wave_sync();
+    // lane l owns bins 32 l .. 32 l + 31; the eight 16-byte reads are rotated by the lane so that
+    // neighbouring lanes use different LDS banks
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < kOwn / 4; ++j) {
+      const int4 c = h4[lane * (kOwn / 4) + ((j + lane) & (kOwn / 4 - 1))];
+      mine += (c.x + c.y) + (c.z + c.w);
+    }
+    int incl = mine;  // suffix sums over the lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int v = __shfl_down(incl, d, 64);
+      if (lane + d < 64) incl += v;
+    }
+    const int above = incl - mine;
+    const uint64_t owner_mask = __ballot(above < remaining && remaining <= above + mine);  // exactly one lane
+    const int owner = owner_mask ? __builtin_ctzll(owner_mask) : 0;
+    const int above_owner = __builtin_amdgcn_readlane(above, owner);
+    // the owner's 32 bins, one per lane of the lower half wave; suffix sums again
+    const int c_bin = lane < kOwn ? hist[owner * kOwn + lane] : 0;
+    int incl_b = c_bin;
+#pragma unroll
+    for (int d = 1; d < kOwn; d <<= 1) {
+      const int v = __shfl_down(incl_b, d, 64);
+      if (lane + d < kOwn) incl_b += v;
+    }
+    const int above_b = above_owner + incl_b - c_bin;  // matching keys with a larger digit
+    const uint64_t bin_mask = __ballot(lane < kOwn && above_b < remaining && remaining <= above_b + c_bin);
+    const int bin_lane = bin_mask ? __builtin_ctzll(bin_mask) : 0;
+    const int cnt = __builtin_amdgcn_readlane(c_bin, bin_lane);
+    remaining -= __builtin_amdgcn_readlane(above_b, bin_lane);
+    prefix |= static_cast<uint32_t>(owner * kOwn + bin_lane) << shift;
+    hi = shift;
+    eq_total = cnt;
+    if (hi > 0 && cnt <= 64) {
+      // the candidates (keys that match the prefix so far), one per lane
+      const uint32_t lo_mask = 0xFFFFFFFFu << hi;
+      int n_cand = 0;
+      wave_sync();  // the histogram has been read
+      auto collect = [&](uint32_t kv, bool m) {
+        const uint64_t bm = __ballot(m);
+        if (bm != 0) {  // wave-uniform
+          const int at = lanes_below(bm, n_cand);
+          if (m && at < 64) cand[at] = kv;
+          n_cand += popc64(bm);
+        }
+      };
+      collect(key_r, in_tail && (key_r & lo_mask) == prefix);
+      rows_down_from(n_full, [&](int i) { collect(key[i], (key[i] & lo_mask) == prefix); });
+      wave_sync();
+      n_cand = min(n_cand, 64);
+      const bool has = lane < n_cand;
+      const uint32_t my = has ? cand[lane] : 0u;
+      int gt = 0, ge = 0;
+      for (int c = 0; c < n_cand; ++c) {
+        const uint32_t x = __builtin_amdgcn_readlane(my, c);
+        gt += x > my ? 1 : 0;
+        ge += x >= my ? 1 : 0;
+      }
+      const uint64_t thr_mask = __ballot(has && gt < remaining && remaining <= ge);  // the lanes holding the threshold
+      const int thr_lane = thr_mask ? __builtin_ctzll(thr_mask) : 0;
+      prefix = __builtin_amdgcn_readlane(my, thr_lane);
+      const int gt_t = __builtin_amdgcn_readlane(gt, thr_lane), ge_t = __builtin_amdgcn_readlane(ge, thr_lane);
+      remaining -= gt_t;
+      eq_total = ge_t - gt_t;
+      hi = 0;
+    }
+  }
+  // `remaining` of the eq_total keys equal to the threshold are taken, lowest index first; rows
+  // are written last to first, `after` counting the kept keys of the rows already written
+  const int lane_start = start + lane;
+  int after = 0;
+  if (eq_total == remaining) {  // all of them: one compare per key
+    auto put = [&](uint32_t kv, bool keep, int row) {
+      const uint64_t bk = __ballot(keep);
+      after += popc64(bk);
+      const int at = lanes_below(bk, k - after);
+      if (keep && static_cast<uint32_t>(at) < static_cast<uint32_t>(k))
+        *reinterpret_cast<int32_t*>(reinterpret_cast<char*>(out) + static_cast<uint32_t>(at) * 4u) = lane_start + row * 64;
+    };
+    put(key_r, in_tail && key_r >= prefix, n_full);
+    rows_down_from(n_full, [&](int i) { put(key[i], key[i] >= prefix, i); });
+  } else {
+    int eq_after = 0;
+    auto put = [&](uint32_t kv, bool valid, int row) {
+      const bool eq = valid && kv == prefix;
+      const uint64_t beq = __ballot(eq);
+      eq_after += popc64(beq);
+      const int eq_at = lanes_below(beq, eq_total - eq_after);  // equal keys at lower indices
+      const bool keep = valid && (kv > prefix || (eq && eq_at < remaining));
+      const uint64_t bk = __ballot(keep);
+      after += popc64(bk);
+      const int at = lanes_below(bk, k - after);
+      if (keep && static_cast<uint32_t>(at) < static_cast<uint32_t>(k))
+        *reinterpret_cast<int32_t*>(reinterpret_cast<char*>(out) + static_cast<uint32_t>(at) * 4u) = lane_start + row * 64;
+    };
+    put(key_r, in_tail, n_full);
+    rows_down_from(n_full, [&](int i) { put(key[i], true, i); });
   }
 }
 
@@ -691,7 +920,11 @@ extern "C" int pc_compact_batch_phase(int phases, int n_layers, void* K, void* V
   const int n_clear = in_place ? static_cast<int>(lay.clear_bytes / sizeof(int32_t)) : 0;
   if (!(phases & PC_COMPACT_SELECT)) {
     // indices and cleared counters come from an earlier SELECT call with the same arguments
-  } else if (max_prune_len <= 256)
+  } else if (max_prune_len > kRowsSelectMinLen && max_prune_len <= PC_MAX_SELECT_LEN &&
+             n_seg * hsel * n_layers >= kRowsSelectMinUnits)
+    select_rows_kernel<<<sgrid, 64, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear, hsel,
+                                             score_stride_l, idx_stride_layer);
+  else if (max_prune_len <= 256)
     select_block_kernel<1><<<sgrid, 256, 0, st>>>(score, score_stride_h, idx, idx_stride, tab, clear, n_clear, hsel,
                                                    score_stride_l, idx_stride_layer);
   else if (max_prune_len <= 1024)

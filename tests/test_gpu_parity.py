@@ -658,6 +658,67 @@ def test_compact_batch_equals_layer_by_layer_and_the_oracle(in_place, share):
 
 
 @pytest.mark.parametrize("in_place", [False, True])
+def test_compact_batch_with_many_long_segments_takes_the_wave_per_segment_select(in_place):
+    # 4 layers x 4 heads x 101 segments = 1,616 selections in one call, the longest 4,096 rows:
+    # the stack form of the select (one wave per segment).  Given fp32 scores, so the kept sets
+    # are exact: ragged and 64-aligned lengths, heavy ties, an all-equal frame, -0 against +0,
+    # negative and -inf scores, budgets 0, 1, len - 1 and len.
+    rng = np.random.default_rng(77)
+    L, Hkv, D = 4, 4, 128
+    lens = [int(v) for v in rng.integers(1025, 2300, 100)]
+    lens[0], lens[1], lens[2], lens[3], lens[4] = 4096, 4032, 1088, 1025, 2047
+    segs, at = [(0, 24, pk.PC_SEG_TEXT, -1)], 24
+    for f, n in enumerate(lens):
+        segs.append((at, n, pk.PC_SEG_FRAME, f))
+        at += n
+    nk = at
+    budgets = [24] + [int(rng.integers(1, n)) for n in lens]
+    budgets[1], budgets[2], budgets[3], budgets[4], budgets[5] = 4095, 1, 0, 1024, 2047   # the last: nothing pruned
+    budgets[6] = lens[5] + 7                                      # beyond the length: kept whole
+    sc = rng.standard_normal((L, Hkv, nk)).astype(np.float32)
+    sc[0] = np.exp(sc[0] * 1.5 - 6)                               # column-mass-like, one shared exponent range
+    sc[1] = (rng.integers(0, 5, (Hkv, nk)) / 4.0).astype(np.float32)      # heavy ties
+    s7 = segs[7]
+    sc[2, :, s7[0]:s7[0] + s7[1]] = 0.125                         # one frame all equal
+    s8 = segs[8]
+    sc[2, :, s8[0]:s8[0] + 600] = 0.0
+    sc[2, :, s8[0]:s8[0] + 600:2] = -0.0                          # -0 ties with +0
+    s9 = segs[9]
+    sc[3, :, s9[0]:s9[0] + s9[1]:3] = -np.inf                     # masked-style scores
+    K = torch.randn((L, Hkv, nk, D), dtype=torch.bfloat16, device=DEV)
+    V = torch.randn_like(K)
+    pos = torch.randint(0, 1000, (L, Hkv, nk, 3), dtype=torch.int32, device=DEV)
+    scd = dev(sc, None)
+    plan, nk_out = pk.pc_compact_plan(segs, budgets)
+    assert plan == orc.packed_segments(segs, budgets)
+    idx = torch.full((L, Hkv, nk_out), -1, dtype=torch.int32, device=DEV)
+    ref = []
+    for l in range(L):                                            # one call per layer (the work-group form), out of place
+        Ko = torch.empty((Hkv, nk_out, D), dtype=K.dtype, device=DEV)
+        Vo, po = torch.empty_like(Ko), torch.empty((Hkv, nk_out, 3), dtype=torch.int32, device=DEV)
+        io = torch.empty((Hkv, nk_out), dtype=torch.int32, device=DEV)
+        pk.pc_compact(K[l], V[l], pos[l], scd[l], segs, budgets, out=(Ko, Vo, po), idx=io)
+        ref.append((Ko, Vo, po, io))
+    if in_place:
+        segs_out, nko = pk.pc_compact_batch(K, V, pos, scd, segs, budgets, idx=idx)
+        Kb, Vb, pb = K[:, :, :nko], V[:, :, :nko], pos[:, :, :nko]
+    else:
+        Kb = torch.empty((L, Hkv, nk_out, D), dtype=K.dtype, device=DEV)
+        Vb, pb = torch.empty_like(Kb), torch.empty((L, Hkv, nk_out, 3), dtype=torch.int32, device=DEV)
+        segs_out, nko = pk.pc_compact_batch(K, V, pos, scd, segs, budgets, out=(Kb, Vb, pb), idx=idx)
+    assert segs_out == plan and nko == nk_out
+    ig = host(idx)
+    for l in range(L):
+        for h in range(Hkv):
+            want = np.concatenate([
+                np.arange(s, s + n) if kind != pk.PC_SEG_FRAME else s + orc.select_topk(sc[l, h, s:s + n], min(n, b))
+                for (s, n, kind, _), b in zip(segs, budgets)])
+            assert np.array_equal(ig[l, h], want), (l, h)
+        Ko, Vo, po, io = ref[l]
+        assert torch.equal(idx[l], io) and torch.equal(Kb[l], Ko) and torch.equal(Vb[l], Vo) and torch.equal(pb[l], po)
+
+
+@pytest.mark.parametrize("in_place", [False, True])
 def test_select_and_gather_as_two_calls_on_two_streams(in_place):
     # the select half on a side stream, the gather half on the main stream behind an event:
     # same result, bit for bit, as the single call
