@@ -10,6 +10,8 @@ Each step is compared with the fp64 oracle on identical input bits:
     as in the frame-48 compaction runs, for gamma in {0.7, 0.85, 0.95};
   * pc_frame_attn, packed and dense, on 64 sampled query rows per head over all keys
     (max |err| <= 2e-2, mean |err| <= 2e-3), and its log-sum-exp output.
+The stack call (pc_compact_batch, 8 layers at frame 48, in place) is compared with the per-layer
+call bit for bit and with the oracle's top-k.
 The rolling step (cache packed in place over several frame steps) is checked at the 28-layer
 rollout's shape, 24 query / 8 KV heads, each step starting from the oracle's previous state.
 The steps after the rotation read the ORACLE's rotated bits, so that every step is judged on
@@ -128,6 +130,52 @@ def test_full_size_frame(frame, fold):
     err = np.abs(host(O)[:, rs].astype(np.float64) - Ow)
     assert err.max() <= 2e-2 and err.mean() <= 2e-3, (err.max(), err.mean())
     assert np.abs(host(lse)[:, rs] - Lw).max() <= 1e-3
+
+
+@pytest.mark.parametrize("gamma", [0.7, 0.95])
+def test_full_size_stack_compaction_equals_layer_by_layer_and_the_oracle(gamma):
+    """pc_compact_batch at frame 48 as bench.py's batched leg runs it (4 KV heads, 193,792 rows,
+    in place), on 8 layers drawn on the device from their own seeds: 1,568 selections in one
+    call, which takes the one-wave-per-segment select.  Every layer must come out bit for bit as
+    one pc_compact call per layer leaves it (the form the test above checks against the oracle),
+    and the index sets of the first and last layer are compared with the oracle's top-k on the
+    same fp32 scores (exact: no band)."""
+    L, Hq, Hkv, D, n_past, n_text, gh, gw = 8, 16, 4, 128, 47, 256, 48, 84
+    n = gh * gw
+    Nk = n_text + n * (1 + n_past)
+    segments = synth.segment_table(n_text, n, n_past)
+    rows = dev(synth.strided_rows(n, 512).astype(np.int32), None)
+    pos_k = synth.cache_positions(n_text, gh, gw, n_past)
+    KL = torch.empty((L, Hkv, Nk, D), dtype=torch.bfloat16, device=DEV)
+    VL = torch.empty_like(KL)
+    PL = dev(np.broadcast_to(pos_k[None, None], (L, Hkv, Nk, 3)).copy(), None)
+    SL = torch.empty((L, Hkv, Nk), dtype=torch.float32, device=DEV)
+    Q = torch.empty((Hq, n, D), dtype=torch.bfloat16, device=DEV)
+    for l in range(L):
+        synth.device_frame_layer(4000 + l, n_past, KL[l], VL[l], Q)
+        pk.pc_score(Q, KL[l], Nk, D ** -0.5, score=SL[l], q_rows=rows)
+    b = pk.pc_budget(pk.PC_BUDGET_POW, n, n_past, gamma, 512)
+    assert b == orc.budget_pow(n, n_past, gamma, 512)
+    budgets = pk.segment_budgets(segments, b)
+    plan, nk_out = pk.pc_compact_plan(segments, budgets)
+    ref = []
+    for l in range(L):                                   # one call per layer, out of place
+        Ko = torch.empty((Hkv, nk_out, D), dtype=KL.dtype, device=DEV)
+        Vo, po = torch.empty_like(Ko), torch.empty((Hkv, nk_out, 3), dtype=torch.int32, device=DEV)
+        io = torch.empty((Hkv, nk_out), dtype=torch.int32, device=DEV)
+        pk.pc_compact(KL[l], VL[l], PL[l], SL[l], segments, budgets, out=(Ko, Vo, po), idx=io)
+        ref.append((Ko, Vo, po, io))
+    idx = torch.full((L, Hkv, nk_out), -1, dtype=torch.int32, device=DEV)
+    segs, nk = pk.pc_compact_batch(KL, VL, PL, SL, segments, budgets, idx=idx)       # in place
+    assert segs == plan and nk == nk_out
+    for l in range(L):
+        Ko, Vo, po, io = ref[l]
+        assert torch.equal(idx[l], io), l
+        assert torch.equal(KL[l, :, :nk], Ko) and torch.equal(VL[l, :, :nk], Vo) and torch.equal(PL[l, :, :nk], po), l
+    for l in (0, L - 1):
+        n_ex = check_selection(host(idx[l]), host(SL[l]).astype(np.float64), segments, budgets, band=0.0)
+        assert n_ex == 0
+    print(f"stack compaction gamma={gamma} ok, Nk_packed={nk}", flush=True)
 
 
 def test_rolling_steps_at_full_frame_size():
