@@ -392,9 +392,9 @@ __global__ __launch_bounds__(64) void select_rows_kernel(
   {  // every load in flight before the first use; rows past n_full are neither loaded nor looked at
     float v[kRows];
     const float v_r = sc[min(n_full * 64 + lane, len - 1)];
-    // a buffer descriptor over the segment's scores (raw 32-bit data; reads past `len` return 0): the
-    // row offset is a scalar operand of the load and the lane's byte offset one register for all
-    // rows, so a load costs no vector address arithmetic
+    // a buffer descriptor that spans exactly the segment's scores (raw 32-bit data): the row offset
+    // is a scalar operand of the load and the lane's byte offset one register for all rows, so a
+    // load costs no vector address arithmetic; only rows that lie inside the segment are loaded
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(sc), 0, len * 4, 0x00020000);
     const int lane_bytes = lane * 4;
@@ -518,15 +518,15 @@ __global__ __launch_bounds__(64) void select_rows_kernel(
   const int lane_start = start + lane;
   int after = 0;
   if (eq_total == remaining) {  // all of them: one compare per key
-    auto put = [&](uint32_t kv, bool keep, int row) {
+    auto put = [&](bool keep, int row) {
       const uint64_t bk = __ballot(keep);
       after += popc64(bk);
       const int at = lanes_below(bk, k - after);
       if (keep && static_cast<uint32_t>(at) < static_cast<uint32_t>(k))
         *reinterpret_cast<int32_t*>(reinterpret_cast<char*>(out) + static_cast<uint32_t>(at) * 4u) = lane_start + row * 64;
     };
-    put(key_r, in_tail && key_r >= prefix, n_full);
-    rows_down_from(n_full, [&](int i) { put(key[i], key[i] >= prefix, i); });
+    put(in_tail && key_r >= prefix, n_full);
+    rows_down_from(n_full, [&](int i) { put(key[i] >= prefix, i); });
   } else {
     int eq_after = 0;
     auto put = [&](uint32_t kv, bool valid, int row) {
