@@ -53,6 +53,32 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 
 __device__ __forceinline__ int popc64(uint64_t v) { return __popcll(v); }
 
+// Inclusive scan over the 64 lanes (lane l gets op over lanes 0..l) with data-parallel-primitive
+// moves: shifts by 1, 2, 4, 8 inside each row of 16 lanes, then lane 15 of a row into the row
+// after it and lane 31 into the upper half.  Each step is one vector instruction; a shuffle
+// through the LDS crossbar costs a round trip of a hundred cycles per step.
+template <class Op>
+__device__ __forceinline__ int wave_scan(int x, int identity, Op op) {
+  x = op(x, __builtin_amdgcn_update_dpp(identity, x, 0x111, 0xf, 0xf, false));  // row_shr:1
+  x = op(x, __builtin_amdgcn_update_dpp(identity, x, 0x112, 0xf, 0xf, false));  // row_shr:2
+  x = op(x, __builtin_amdgcn_update_dpp(identity, x, 0x114, 0xf, 0xf, false));  // row_shr:4
+  x = op(x, __builtin_amdgcn_update_dpp(identity, x, 0x118, 0xf, 0xf, false));  // row_shr:8
+  x = op(x, __builtin_amdgcn_update_dpp(identity, x, 0x142, 0xa, 0xf, false));  // row_bcast:15 -> rows 1, 3
+  x = op(x, __builtin_amdgcn_update_dpp(identity, x, 0x143, 0xc, 0xf, false));  // row_bcast:31 -> rows 2, 3
+  return x;
+}
+__device__ __forceinline__ int wave_prefix_sum(int x) {  // sum over lanes 0..l
+  return wave_scan(x, 0, [](int a, int b) { return a + b; });
+}
+__device__ __forceinline__ uint32_t wave_or(uint32_t x) {  // OR over the wave, in every lane
+  const int r = wave_scan(static_cast<int>(x), 0, [](int a, int b) { return a | b; });
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(r, 63));
+}
+__device__ __forceinline__ uint32_t wave_and(uint32_t x) {
+  const int r = wave_scan(static_cast<int>(x), -1, [](int a, int b) { return a & b; });
+  return static_cast<uint32_t>(__builtin_amdgcn_readlane(r, 63));
+}
+
 // One wave selects the top `k` of `len` scores.  Keys are register resident when
 // kItems > 0 (len <= 64 * kItems); kItems == 0 re-reads the scores on every pass.
 template <int kItems>
@@ -213,11 +239,8 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
       k_or |= key[i];
     }
   }
-#pragma unroll
-  for (int d = 32; d > 0; d >>= 1) {
-    k_and &= __shfl_xor(k_and, d, 64);
-    k_or |= __shfl_xor(k_or, d, 64);
-  }
+  k_and = wave_and(k_and);
+  k_or = wave_or(k_or);
   if (lane == 0) {
     s_and[wave] = k_and;
     s_or[wave] = k_or;
@@ -248,12 +271,8 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
 #pragma unroll
     for (int j = 0; j < kOwn; ++j) mine += c[j];
     // suffix sums over the threads: above = matching keys with a digit beyond this thread's bins
-    int incl = mine;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const int v = __shfl_down(incl, d, 64);
-      if (lane + d < 64) incl += v;
-    }
+    const int upto = wave_prefix_sum(mine);
+    const int incl = __builtin_amdgcn_readlane(upto, 63) - upto + mine;  // this lane and the lanes above it
     if (lane == 0) s_wave_sum[wave] = incl;
     __syncthreads();
     int above = incl - mine;
@@ -295,12 +314,7 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
     const bool valid = e0 + i < len;
     mine += (valid && key[i] > prefix ? 1 : 0) + (valid && key[i] == prefix ? 1 << 16 : 0);
   }
-  int incl = mine;  // inclusive prefix sum over the lanes below
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const int v = __shfl_up(incl, d, 64);
-    if (lane >= d) incl += v;
-  }
+  const int incl = wave_prefix_sum(mine);  // this lane and the lanes below it
   __syncthreads();  // s_wave_sum is free again
   if (lane == 63) s_wave_sum[wave] = incl;
   __syncthreads();
@@ -412,9 +426,7 @@ __global__ __launch_bounds__(64) void select_rows_kernel(
   const uint32_t key0 = __builtin_amdgcn_readfirstlane(n_full > 0 ? key[0] : key_r);
   uint32_t differ = in_tail ? key_r ^ key0 : 0u;
   rows_down_from(n_full, [&](int i) { differ |= key[i] ^ key0; });
-#pragma unroll
-  for (int d = 32; d > 0; d >>= 1) differ |= __shfl_xor(differ, d, 64);
-  differ = __builtin_amdgcn_readfirstlane(differ);  // the same in every lane: scalar from here on
+  differ = wave_or(differ);  // the same in every lane: scalar from here on
   int hi = differ ? 32 - __clz(differ) : 0;  // number of undecided low bits
   uint32_t prefix = hi >= 32 ? 0u : (key0 >> hi) << hi;
   int remaining = k;   // rank of the threshold among the keys that match the prefix
@@ -453,25 +465,15 @@ __global__ __launch_bounds__(64) void select_rows_kernel(
       const int4 c = h4[lane * (kOwn / 4) + ((j + lane) & (kOwn / 4 - 1))];
       mine += (c.x + c.y) + (c.z + c.w);
     }
-    int incl = mine;  // suffix sums over the lanes
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const int v = __shfl_down(incl, d, 64);
-      if (lane + d < 64) incl += v;
-    }
-    const int above = incl - mine;
+    const int upto = wave_prefix_sum(mine);
+    const int above = __builtin_amdgcn_readlane(upto, 63) - upto;  // votes in the bins of the lanes above
     const uint64_t owner_mask = __ballot(above < remaining && remaining <= above + mine);  // exactly one lane
     const int owner = owner_mask ? __builtin_ctzll(owner_mask) : 0;
     const int above_owner = __builtin_amdgcn_readlane(above, owner);
     // the owner's 32 bins, one per lane of the lower half wave; suffix sums again
     const int c_bin = lane < kOwn ? hist[owner * kOwn + lane] : 0;
-    int incl_b = c_bin;
-#pragma unroll
-    for (int d = 1; d < kOwn; d <<= 1) {
-      const int v = __shfl_down(incl_b, d, 64);
-      if (lane + d < kOwn) incl_b += v;
-    }
-    const int above_b = above_owner + incl_b - c_bin;  // matching keys with a larger digit
+    const int upto_b = wave_prefix_sum(c_bin);
+    const int above_b = above_owner + __builtin_amdgcn_readlane(upto_b, kOwn - 1) - upto_b;  // matching keys with a larger digit
     const uint64_t bin_mask = __ballot(lane < kOwn && above_b < remaining && remaining <= above_b + c_bin);
     const int bin_lane = bin_mask ? __builtin_ctzll(bin_mask) : 0;
     const int cnt = __builtin_amdgcn_readlane(c_bin, bin_lane);
