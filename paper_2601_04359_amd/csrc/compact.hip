@@ -10,7 +10,7 @@
 //            segment instead: fewer instructions per key and no work-group barriers
 //            (5,488 segments: 56 us -> 34 us; one layer's 196 segments: 10 us -> 15 us, hence
 //            the switch-over at 1,536 segments).
-//   gather   HBM-bound.  A work-group owns 64 consecutive packed rows of one
+//   gather   HBM-bound.  A work-group owns 128 consecutive packed rows of one
 //            KV head: it loads its K, V and position rows (16 bytes per lane), then stores
 //            them.  In place, a work-group may only store once every work-group whose SOURCE
 //            rows lie in its destination range has finished loading.  Work-groups take their
@@ -30,10 +30,11 @@ namespace {
 
 // Packed rows per gather work-group and its size: a thread moves two 16-byte pieces of K and two
 // of V.  Measured on 28 layer caches at frame 48 (gamma 0.85): 4 pieces per thread (64 rows, 256
-// threads) 931 us, 2 pieces (32 rows, 256 threads) 838 us, (64 rows, 512 threads) 812 us, 1 piece
-// (32 rows, 512 threads) 931 us.
-constexpr int kGatherRows = 64;
-constexpr int kGatherThreads = 512;
+// threads) 931 us, 2 pieces (32 rows, 256 threads) 838 us, (64 rows, 512 threads) 812 us,
+// (128 rows, 1,024 threads) 807 us, 1 piece (32 rows, 512 threads) 931 us.  One layer per call
+// gains most from the largest shape (40.8 against 42.4 us per layer at gamma 0.7).
+constexpr int kGatherRows = 128;
+constexpr int kGatherThreads = 1024;
 constexpr int kSpinLimit = 1 << 22;
 
 struct SegTable {
