@@ -170,8 +170,8 @@ __global__ __launch_bounds__(64) void select_kernel(const float* __restrict__ sc
 //     vote into a 2,048-bin LDS histogram; a thread owns eight neighbouring bins, the 256 threads
 //     take a suffix sum over their totals (wave scan + one exchange) and the thread whose bins
 //     contain the k-th key walks its eight.  With 4,032 keys over 2,048 bins the chosen bin
-//     nearly always holds a single key, which then IS the threshold and ends the search; two
-//     passes are the usual worst case.
+//     nearly always holds a handful of keys: up to 64 are put into LDS and ranked against each
+//     other by every wave (no second pass over the histogram); more than 64 take another pass.
 //   * Output in ascending index order: with consecutive keys per thread a kept key's position is
 //     (kept keys of lower threads) + (kept keys earlier in this thread), so one more scan over
 //     the threads (keys above the threshold and keys equal to it, packed in one word) places
@@ -190,8 +190,10 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
   static_assert(kOwn == 8, "a thread reads its bins with two 16-byte loads");
   __shared__ __align__(16) int s_hist[kBins];
   __shared__ int s_wave_sum[4];
-  __shared__ int s_pick[4];  // chosen digit, keys above it, keys in it, the key when it is alone
+  __shared__ int s_pick[3];  // chosen digit, keys above it, keys in it
   __shared__ uint32_t s_and[4], s_or[4];
+  __shared__ uint32_t s_cand[64];  // the keys of the chosen bin when they are few
+  __shared__ int s_n_cand;
   const int s = blockIdx.x, h = blockIdx.y;
   {
     const int nb = gridDim.x * gridDim.y, b = h * gridDim.x + s;
@@ -246,6 +248,10 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
     s_and[wave] = k_and;
     s_or[wave] = k_or;
   }
+  int4* h4 = reinterpret_cast<int4*>(s_hist);
+  h4[2 * t] = make_int4(0, 0, 0, 0);  // this thread's own eight bins, cleared for the first pass
+  h4[2 * t + 1] = make_int4(0, 0, 0, 0);
+  if (t == 0) s_n_cand = 0;
   __syncthreads();
   k_and = s_and[0] & s_and[1] & s_and[2] & s_and[3];
   k_or = s_or[0] | s_or[1] | s_or[2] | s_or[3];
@@ -253,12 +259,15 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
   int hi = differ ? 32 - __clz(differ) : 0;  // number of undecided low bits
   uint32_t prefix = hi >= 32 ? 0u : (k_or >> hi) << hi;
   int remaining = k;
-  int4* h4 = reinterpret_cast<int4*>(s_hist);
+  bool cleared = true;
   while (hi > 0) {
     const int width = min(kBits, hi), shift = hi - width;
-    h4[2 * t] = make_int4(0, 0, 0, 0);  // this thread's own eight bins
-    h4[2 * t + 1] = make_int4(0, 0, 0, 0);
-    __syncthreads();
+    if (!cleared) {  // a further pass (rare): the bins are cleared behind the reads of the pass before
+      h4[2 * t] = make_int4(0, 0, 0, 0);
+      h4[2 * t + 1] = make_int4(0, 0, 0, 0);
+      __syncthreads();
+    }
+    cleared = false;
     const uint32_t hi_mask = hi >= 32 ? 0u : 0xFFFFFFFFu << hi;
     const uint32_t digit_mask = (1u << width) - 1u;
 #pragma unroll
@@ -298,14 +307,32 @@ __global__ __launch_bounds__(256) void select_block_kernel(const float* __restri
     prefix |= static_cast<uint32_t>(s_pick[0]) << shift;
     remaining -= s_pick[1];
     hi = shift;
-    if (s_pick[2] == 1 && hi > 0) {  // block-uniform: the bin's only key is the k-th largest
+    if (hi > 0 && s_pick[2] <= 64) {
+      // block-uniform: the chosen bin holds few keys (with 4,032 keys over 2,048 bins nearly always).
+      // They go to LDS, and every wave ranks them for itself: lane j counts the candidates above and
+      // not below its own; the lane whose counts bracket the remaining rank holds the threshold.
       const uint32_t lo_mask = 0xFFFFFFFFu << hi;
 #pragma unroll
       for (int i = 0; i < kItems; ++i)
-        if (e0 + i < len && (key[i] & lo_mask) == prefix) s_pick[3] = static_cast<int>(key[i]);
+        if (e0 + i < len && (key[i] & lo_mask) == prefix) {
+          const int at = atomicAdd(&s_n_cand, 1);
+          if (at < 64) s_cand[at] = key[i];
+        }
       __syncthreads();
-      prefix = static_cast<uint32_t>(s_pick[3]);
-      hi = 0;  // remaining is 1 here: the key itself is taken
+      const int n_cand = min(s_n_cand, 64);
+      const bool has = lane < n_cand;
+      const uint32_t my = has ? s_cand[lane] : 0u;
+      int gt = 0, ge = 0;
+      for (int j = 0; j < n_cand; ++j) {
+        const uint32_t x = __builtin_amdgcn_readlane(my, j);
+        gt += x > my ? 1 : 0;
+        ge += x >= my ? 1 : 0;
+      }
+      const uint64_t thr_mask = __ballot(has && gt < remaining && remaining <= ge);
+      const int thr_lane = thr_mask ? __builtin_ctzll(thr_mask) : 0;
+      prefix = __builtin_amdgcn_readlane(my, thr_lane);
+      remaining -= __builtin_amdgcn_readlane(gt, thr_lane);  // of the keys equal to the threshold, this many are taken
+      hi = 0;
     }
   }
   // keys above the threshold (low half-word) and equal to it (high half-word) in this thread
